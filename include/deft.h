@@ -1,0 +1,183 @@
+/*
+ * deft.h -- C ABI of the DEFT gradient-selection library for AMD MI355X (gfx950).
+ *
+ * The library covers the sparsifier of "DEFT: Exploiting Gradient Norm Difference between
+ * Model Layers for Scalable Gradient Sparsification" (Yoon & Oh, ICPP 2023), Sec. 4:
+ *   1) two-stage gradient vector partitioning            (Alg. 2, Sec. 4.1)   host
+ *   2) per-layer gradient norm + local k assignment      (Alg. 3, Sec. 4.2)   device + host
+ *   3) bin-packing layer allocation to workers           (Alg. 4, Sec. 4.3)   host
+ *   4) layer-wise Top-k selection on the worker's layers (Alg. 5, Sec. 4.4)   device
+ * and the conventional Top-k over the whole vector (Sec. 1, Sec. 3.1) as comparison path.
+ *
+ * Conventions
+ *   - The gradient vector g is flat fp32 in device memory, N = n_g elements, N < 2^31, and
+ *     its base address is 16-byte aligned.  Layer l is g[offsets[l] .. offsets[l+1]).
+ *   - "_dev" pointers are device memory (or host memory the device can access, where
+ *     noted); "_host" pointers and unmarked pointers of the host-only calls are ordinary
+ *     host memory.  The caller owns every buffer.  The library allocates and frees no
+ *     device memory and keeps no state between calls.
+ *   - Device calls only enqueue work on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream).  They never synchronise; outputs are valid once the caller has
+ *     synchronised the stream.  The workspace must stay untouched until then.  Host
+ *     arrays passed to a device call are consumed before it returns.
+ *   - Every call returns a status: DEFT_OK (0) or a negative code.  On DEFT_EINVAL,
+ *     DEFT_ERANGE, DEFT_EWS and DEFT_ECAP nothing has been written or enqueued.
+ *   - Magnitudes are compared through the integer key (bit pattern & 0x7fffffff): exact
+ *     order of |g| for all non-NaN values, -0 equal to +0, NaN above infinity.  Among equal
+ *     magnitudes the lower index is selected first.  Selected entries are reported in
+ *     ascending index order with their original bit pattern.
+ *   - Results are deterministic: the same inputs give the same bits.
+ */
+#ifndef DEFT_H
+#define DEFT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DEFT_OK 0
+#define DEFT_EINVAL (-1) /* null pointer, bad count, bad density/rank, malformed offsets or k */
+#define DEFT_ERANGE (-2) /* N >= 2^31: indices are 32-bit */
+#define DEFT_EWS (-3)    /* workspace too small (see deft_workspace_bytes) */
+#define DEFT_ECAP (-4)   /* output capacity too small */
+#define DEFT_EHIP (-5)   /* HIP launch/runtime error */
+
+#define DEFT_OP_NORMS 0
+#define DEFT_OP_SELECT 1
+#define DEFT_OP_TOPK_GLOBAL 2
+
+/* Static, human-readable text for a status code. */
+const char* deft_strerror(int status);
+
+/*
+ * Alg. 2 (Sec. 4.1): tensor sizes -> layer offsets.  A tensor holding more than n_g/n_workers
+ * elements is cut into n_workers contiguous fractions whose sizes differ by at most one
+ * (larger first); other tensors become one layer.  Empty tensors/fractions yield no layer.
+ *   tensor_sizes[T]  in   sizes in model order (>= 0); n_g is their sum
+ *   offsets[cap+1]   out  offsets[0] = 0 ... offsets[L] = n_g
+ *   layer_tensor[cap] out (may be NULL) source tensor of each layer
+ *   cap              in   capacity in layers; T * n_workers always suffices
+ *   L_out            out  number of layers
+ * Errors: DEFT_EINVAL (null, T < 0, n_workers < 1, negative size), DEFT_ECAP (cap too small),
+ * DEFT_ERANGE (n_g >= 2^31).
+ */
+int deft_partition(const int64_t* tensor_sizes, int32_t T, int32_t n_workers, int64_t* offsets,
+                   int32_t* layer_tensor, int32_t cap, int32_t* L_out);
+
+/*
+ * Host-side validation of a layer layout: offsets[0] == 0, non-decreasing, offsets[L] == N,
+ * 1 <= L, 0 <= N < 2^31.  Returns DEFT_OK, DEFT_EINVAL or DEFT_ERANGE.
+ */
+int deft_check_layout(const int64_t* offsets_host, int32_t L, int64_t N);
+
+/*
+ * Sec. 4.2, first sentence of its second paragraph: the gradient norm of each layer.
+ * Enqueues one streaming pass over g that writes sumsq[l] = sum of g_i^2 over layer l,
+ * accumulated in fp64 (the square of an fp32 value is exact in fp64) with a fixed
+ * reduction order.  The L2 norm is sqrt(sumsq[l]), taken by the caller.
+ *   g_dev          in   N floats, device, 16-byte aligned
+ *   offsets_dev    in   L+1 int64, device; must satisfy deft_check_layout (not re-checked on
+ *                       the device: malformed offsets give meaningless sums, never an
+ *                       out-of-range access)
+ *   sumsq_dev      out  L doubles; device memory or pinned host memory mapped to the device
+ *   ws_dev         scratch, deft_workspace_bytes(DEFT_OP_NORMS, N, L) bytes, 16-byte aligned
+ * Errors: DEFT_EINVAL, DEFT_ERANGE, DEFT_EWS, DEFT_EHIP.
+ */
+int deft_layer_norms(const float* g_dev, int64_t N, const int64_t* offsets_dev, int32_t L,
+                     double* sumsq_dev, void* ws_dev, size_t ws_bytes, void* stream);
+
+/*
+ * norms[l] = sqrt(sumsq[l]) on the host (IEEE correctly-rounded square root): the step between
+ * deft_layer_norms and deft_alloc_k.  In-place use (norms == sumsq) is allowed.
+ * Errors: DEFT_EINVAL (null, L < 1, negative or NaN entry).
+ */
+int deft_norms_from_sumsq(const double* sumsq, int32_t L, double* norms);
+
+/*
+ * Alg. 3 (Sec. 4.2): local k of every layer.  k_remain starts at K = floor(N*d + 0.5).
+ * Layers are served by descending norm (equal norms: lower position first); each receives
+ * floor(k_remain * norm / norm_remain), at least 1 and at most its size, where norm_remain is
+ * the sum of the norms of the layers not yet served.  All arithmetic is IEEE fp64 without
+ * fused multiply-add.  The sum of k is K unless the lower/upper clamps bind on the tail.
+ *   norms[L]  in   L2 norms (not squared), finite, >= 0
+ *   sizes[L]  in   layer sizes, >= 1
+ *   k_out[L]  out  1 <= k_out[l] <= sizes[l], by layer position
+ * Errors: DEFT_EINVAL (null, L < 1, size < 1, negative or non-finite norm, d outside (0,1],
+ * N < 1).
+ */
+int deft_alloc_k(const double* norms, const int64_t* sizes, int32_t L, int64_t N, double d,
+                 int64_t* k_out);
+
+/*
+ * Alg. 4 (Sec. 4.3, Eq. 3): cost c_x = size_x * ln(k_x); the costliest unplaced layer (lowest
+ * position among equals) goes to the lightest bin (lowest id among equals) until all are
+ * placed.  The caller's bin is (iteration % n_workers + rank) % n_workers.  The broadcast of
+ * the bins by the delegated worker is left to the caller (every caller can compute them).
+ *   sizes[L], k[L]   in   sizes >= 1, 1 <= k <= size
+ *   owner_bin[L]     out  bin id of each layer (the 4L-byte payload of Sec. 4.3)
+ *   my_layers[L]     out  layers of the caller's bin in the order they were placed
+ *   my_count         out  how many
+ * Errors: DEFT_EINVAL (null, L < 1, n_workers < 1, rank outside [0,n), iteration < 0, bad k).
+ */
+int deft_assign_layers(const int64_t* sizes, const int64_t* k, int32_t L, int32_t n_workers,
+                       int64_t iteration, int32_t rank, int32_t* owner_bin, int32_t* my_layers,
+                       int32_t* my_count);
+
+/*
+ * Eq. 4-8: C_i for every bin, C(n) = max_i C_i, f(n), C_trivial(n) and f_trivial(n) for a
+ * given assignment.  out5 = {C(n), f(n), C_trivial(n), f_trivial(n), n_g*ln(K)}.
+ *   C_i[n_workers] out (may be NULL)
+ * Errors: DEFT_EINVAL.
+ */
+int deft_cost_model(const int64_t* sizes, const int64_t* k, const int32_t* owner_bin, int32_t L,
+                    int32_t n_workers, int64_t N, int64_t K, double* C_i, double* out5);
+
+/*
+ * Alg. 5 (Sec. 4.4): for each of the caller's layers, in the given order, the k_l entries of
+ * largest magnitude; indices are global (layer start added).  Segment j of the output holds
+ * layer my_layers[j]: entries seg_off[j] .. seg_off[j+1], ascending index, with the gathered
+ * values (the (index, value) pairs Alg. 1 exchanges afterwards).
+ *   g_dev              in   N floats, device, 16-byte aligned
+ *   offsets_host[L+1]  in   host; must satisfy deft_check_layout (re-checked)
+ *   k_host[L]          in   host; 0 <= k[l] <= size of layer l
+ *   my_layers_host[my_count] in host; layer positions in [0, L); my_count >= 0
+ *   idx_out_dev        out  out_cap int32, device
+ *   val_out_dev        out  out_cap floats, device
+ *   seg_off_host[my_count+1] out host, written before the call returns
+ *   out_cap            in   capacity of idx/val in entries; must be >= sum of the k's
+ *   ws_dev             scratch, deft_workspace_bytes(DEFT_OP_SELECT, share, my_count) bytes
+ *                      where share >= total size of the caller's layers; 16-byte aligned
+ * my_count == 0 is valid and enqueues nothing.
+ * Errors: DEFT_EINVAL, DEFT_ERANGE, DEFT_EWS, DEFT_ECAP, DEFT_EHIP.
+ */
+int deft_select(const float* g_dev, int64_t N, const int64_t* offsets_host, const int64_t* k_host,
+                int32_t L, const int32_t* my_layers_host, int32_t my_count, int32_t* idx_out_dev,
+                float* val_out_dev, int64_t* seg_off_host, int64_t out_cap, void* ws_dev,
+                size_t ws_bytes, void* stream);
+
+/*
+ * Conventional Top-k sparsifier (Sec. 1; the n = 1 case of Sec. 5.4): the K entries of largest
+ * magnitude of the whole vector, ascending index, with values.  0 <= K <= N.
+ *   ws_dev  scratch, deft_workspace_bytes(DEFT_OP_TOPK_GLOBAL, N, 1) bytes, 16-byte aligned
+ * Errors: DEFT_EINVAL, DEFT_ERANGE, DEFT_EWS, DEFT_EHIP.
+ */
+int topk_global(const float* g_dev, int64_t N, int64_t K, int32_t* idx_out_dev,
+                float* val_out_dev, void* ws_dev, size_t ws_bytes, void* stream);
+
+/*
+ * Upper bound on the scratch bytes of a device call.
+ *   DEFT_OP_NORMS:        elems = N,            count = L
+ *   DEFT_OP_SELECT:       elems = total size of the selected layers (N always suffices),
+ *                         count = my_count
+ *   DEFT_OP_TOPK_GLOBAL:  elems = N,            count ignored
+ * Returns 0 for an unknown op or negative arguments.
+ */
+size_t deft_workspace_bytes(int op, int64_t elems, int32_t count);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DEFT_H */

@@ -1,0 +1,194 @@
+// Host side of the DEFT selection path: Alg. 2 (partition), Alg. 3 (local k), Alg. 4
+// (bin-packing) and the cost model of Eq. 3-8.  Integer and IEEE fp64 arithmetic only; this
+// file must be compiled without floating-point contraction so that every product and sum
+// rounds once, in the order written.
+#include "deft.h"
+
+#include <algorithm>
+#include <cmath>
+#include <numeric>
+#include <vector>
+
+namespace {
+constexpr int64_t kMaxN = (int64_t(1) << 31) - 1;
+}
+
+extern "C" const char* deft_strerror(int status) {
+  switch (status) {
+    case DEFT_OK: return "ok";
+    case DEFT_EINVAL: return "invalid argument";
+    case DEFT_ERANGE: return "vector too long: indices are 32-bit, N must be below 2^31";
+    case DEFT_EWS: return "workspace too small";
+    case DEFT_ECAP: return "output capacity too small";
+    case DEFT_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+// Alg. 2.  The test "tensor.size > n_g / n_workers" is evaluated as size * n > n_g, which is
+// the same predicate for integer sizes whether the quotient is taken as real or integer.
+extern "C" int deft_partition(const int64_t* tensor_sizes, int32_t T, int32_t n_workers,
+                              int64_t* offsets, int32_t* layer_tensor, int32_t cap,
+                              int32_t* L_out) {
+  if (!tensor_sizes || !offsets || !L_out || T < 0 || n_workers < 1 || cap < 0) return DEFT_EINVAL;
+  int64_t n_g = 0;
+  for (int32_t t = 0; t < T; ++t) {
+    if (tensor_sizes[t] < 0) return DEFT_EINVAL;
+    n_g += tensor_sizes[t];
+    if (n_g > kMaxN) return DEFT_ERANGE;
+  }
+  // first sweep: count layers so that nothing is written when the capacity is short
+  int64_t need = 0;
+  for (int32_t t = 0; t < T; ++t) {
+    const int64_t s = tensor_sizes[t];
+    if (s == 0) continue;
+    if (s * n_workers > n_g) need += std::min<int64_t>(s, n_workers);
+    else need += 1;
+  }
+  if (need > cap) return DEFT_ECAP;
+  int32_t L = 0;
+  int64_t alloc_pos = 0;
+  offsets[0] = 0;
+  auto emit = [&](int64_t size_layer, int32_t t) {
+    alloc_pos += size_layer;
+    if (layer_tensor) layer_tensor[L] = t;
+    offsets[++L] = alloc_pos;
+  };
+  for (int32_t t = 0; t < T; ++t) {
+    const int64_t s = tensor_sizes[t];
+    if (s == 0) continue;
+    if (s * n_workers > n_g) {
+      const int64_t quotient = s / n_workers;
+      int64_t remainder = s % n_workers;
+      for (int32_t i = 0; i < n_workers; ++i) {
+        int64_t size_layer = quotient;
+        if (remainder > 0) { size_layer += 1; remainder -= 1; }
+        if (size_layer > 0) emit(size_layer, t);
+      }
+    } else {
+      emit(s, t);
+    }
+  }
+  *L_out = L;
+  return DEFT_OK;
+}
+
+extern "C" int deft_check_layout(const int64_t* offsets, int32_t L, int64_t N) {
+  if (!offsets || L < 1 || N < 0) return DEFT_EINVAL;
+  if (N > kMaxN) return DEFT_ERANGE;
+  if (offsets[0] != 0 || offsets[L] != N) return DEFT_EINVAL;
+  for (int32_t l = 0; l < L; ++l)
+    if (offsets[l + 1] < offsets[l]) return DEFT_EINVAL;
+  return DEFT_OK;
+}
+
+extern "C" int deft_norms_from_sumsq(const double* sumsq, int32_t L, double* norms) {
+  if (!sumsq || !norms || L < 1) return DEFT_EINVAL;
+  for (int32_t l = 0; l < L; ++l)
+    if (!(sumsq[l] >= 0.0)) return DEFT_EINVAL;
+  for (int32_t l = 0; l < L; ++l) norms[l] = std::sqrt(sumsq[l]);
+  return DEFT_OK;
+}
+
+// Alg. 3.  norm_remain for the layer served at step j is the sum of the norms from step j to
+// the end, accumulated from the end: the same quantity the listing obtains by subtracting the
+// served norms from the grand total, but free of cancellation, so the last layer's ratio is
+// exactly 1 and no ratio exceeds 1.
+extern "C" int deft_alloc_k(const double* norms, const int64_t* sizes, int32_t L, int64_t N,
+                            double d, int64_t* k_out) {
+  if (!norms || !sizes || !k_out || L < 1 || N < 1) return DEFT_EINVAL;
+  if (!(d > 0.0) || !(d <= 1.0)) return DEFT_EINVAL;
+  for (int32_t l = 0; l < L; ++l) {
+    if (sizes[l] < 1) return DEFT_EINVAL;
+    if (!(norms[l] >= 0.0) || !std::isfinite(norms[l])) return DEFT_EINVAL;
+  }
+  std::vector<int32_t> order(L);
+  std::iota(order.begin(), order.end(), 0);
+  std::stable_sort(order.begin(), order.end(),
+                   [&](int32_t a, int32_t b) { return norms[a] > norms[b]; });
+  std::vector<double> norm_remain(L);
+  double acc = 0.0;
+  for (int32_t j = L - 1; j >= 0; --j) {
+    acc = norms[order[j]] + acc;
+    norm_remain[j] = acc;
+  }
+  int64_t k_remain = (int64_t)std::floor((double)N * d + 0.5);
+  for (int32_t j = 0; j < L; ++j) {
+    const int32_t l = order[j];
+    double k_temp = 0.0;
+    if (norm_remain[j] > 0.0) {
+      const double ratio = norms[l] / norm_remain[j];
+      k_temp = (double)k_remain * ratio;
+    }
+    int64_t k;
+    if ((double)sizes[l] < k_temp) k = sizes[l];
+    else k = std::max<int64_t>(1, (int64_t)std::floor(k_temp));
+    k_out[l] = k;
+    k_remain -= k;
+  }
+  return DEFT_OK;
+}
+
+namespace {
+bool check_sizes_k(const int64_t* sizes, const int64_t* k, int32_t L) {
+  for (int32_t l = 0; l < L; ++l)
+    if (sizes[l] < 1 || k[l] < 1 || k[l] > sizes[l]) return false;
+  return true;
+}
+}  // namespace
+
+// Alg. 4.  The listing rescans the cost list for its maximum and the bin loads for their
+// minimum at every step, taking the first occurrence of each; the same choices are made here
+// by visiting the layers once in (cost descending, position ascending) order.
+extern "C" int deft_assign_layers(const int64_t* sizes, const int64_t* k, int32_t L,
+                                  int32_t n_workers, int64_t iteration, int32_t rank,
+                                  int32_t* owner_bin, int32_t* my_layers, int32_t* my_count) {
+  if (!sizes || !k || !owner_bin || !my_layers || !my_count) return DEFT_EINVAL;
+  if (L < 1 || n_workers < 1 || rank < 0 || rank >= n_workers || iteration < 0) return DEFT_EINVAL;
+  if (!check_sizes_k(sizes, k, L)) return DEFT_EINVAL;
+  const int32_t cycle = (int32_t)(iteration % n_workers);
+  const int32_t curr_part = (cycle + rank) % n_workers;
+  std::vector<double> cost(L);
+  for (int32_t l = 0; l < L; ++l) cost[l] = (double)sizes[l] * std::log((double)k[l]);
+  std::vector<int32_t> order(L);
+  std::iota(order.begin(), order.end(), 0);
+  std::stable_sort(order.begin(), order.end(),
+                   [&](int32_t a, int32_t b) { return cost[a] > cost[b]; });
+  std::vector<double> size_bin(n_workers, 0.0);
+  int32_t cnt = 0;
+  for (int32_t j = 0; j < L; ++j) {
+    const int32_t idx_max = order[j];
+    int32_t bin_min = 0;
+    for (int32_t b = 1; b < n_workers; ++b)
+      if (size_bin[b] < size_bin[bin_min]) bin_min = b;
+    owner_bin[idx_max] = bin_min;
+    size_bin[bin_min] = size_bin[bin_min] + cost[idx_max];
+    if (bin_min == curr_part) my_layers[cnt++] = idx_max;
+  }
+  *my_count = cnt;
+  return DEFT_OK;
+}
+
+// Eq. 4-8.
+extern "C" int deft_cost_model(const int64_t* sizes, const int64_t* k, const int32_t* owner_bin,
+                               int32_t L, int32_t n_workers, int64_t N, int64_t K, double* C_i,
+                               double* out5) {
+  if (!sizes || !k || !owner_bin || !out5 || L < 1 || n_workers < 1 || N < 1 || K < 1)
+    return DEFT_EINVAL;
+  if (!check_sizes_k(sizes, k, L)) return DEFT_EINVAL;
+  std::vector<double> load(n_workers, 0.0);
+  for (int32_t l = 0; l < L; ++l) {
+    if (owner_bin[l] < 0 || owner_bin[l] >= n_workers) return DEFT_EINVAL;
+    load[owner_bin[l]] += (double)sizes[l] * std::log((double)k[l]);
+  }
+  const double C_n = *std::max_element(load.begin(), load.end());
+  const double topk = (double)N * std::log((double)K);
+  const double C_triv = K > n_workers ? ((double)N / n_workers) * std::log((double)K / n_workers) : 0.0;
+  if (C_i) std::copy(load.begin(), load.end(), C_i);
+  out5[0] = C_n;
+  out5[1] = C_n > 0.0 ? topk / C_n : INFINITY;
+  out5[2] = C_triv;
+  out5[3] = C_triv > 0.0 ? topk / C_triv : INFINITY;
+  out5[4] = topk;
+  return DEFT_OK;
+}

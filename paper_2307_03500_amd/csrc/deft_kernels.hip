@@ -1,0 +1,777 @@
+// Device side of the DEFT selection path for gfx950 (MI355X): the per-layer norm pass
+// (Sec. 4.2) and the segmented magnitude Top-k with ordered (index, value) compaction
+// (Alg. 5, Sec. 4.4), which also serves the conventional Top-k over the whole vector (Sec. 1).
+//
+// Both are streaming passes bound by HBM bandwidth: 16-byte loads, 64-lane wavefront
+// reductions/ballots, per-workgroup LDS histograms, no matrix instructions.
+//
+// Selection = exact radix select on the 31-bit key (bits & 0x7fffffff), three digit levels of
+// 11/10/10 bits, then an ordered compaction:
+//   hist(level) -> find(level)   x3     threshold key T and tie quota r per segment
+//   count -> scan -> emit               per-chunk counts, exclusive prefix, ordered write
+// An element is selected iff key > T, or key == T and fewer than r equal keys precede it in
+// its segment.  Every pass walks the segments in fixed-size chunks; a chunk never spans two
+// segments, so small layers simply own short chunks and large layers are split over many
+// workgroups.
+#include "deft.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <vector>
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+constexpr int64_t kMaxN = (int64_t(1) << 31) - 1;
+
+// ------------------------------------------------------------------------------------------
+// reductions
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+  return v;  // valid in lane 0
+}
+
+// Sum over the workgroup in a fixed order; result in every thread.
+__device__ __forceinline__ double block_sum(double v, double* red) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return ((red[0] + red[1]) + red[2]) + red[3];
+}
+
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+  return v;
+}
+
+// ------------------------------------------------------------------------------------------
+// norm pass (Sec. 4.2): sumsq[l] = sum over layer l of g^2, fp64
+// ------------------------------------------------------------------------------------------
+constexpr int kNormIters = 8;                              // 16-byte loads per thread
+constexpr int kNormChunk = kThreads * 4 * kNormIters;      // elements per workgroup
+
+// Largest l in [0, L-1] with off[l] <= x (off[0] == 0 <= x).
+__device__ __forceinline__ int layer_of(const int64_t* __restrict__ off, int L, int64_t x) {
+  int lo = 0, hi = L;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (off[mid] <= x) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// The vector is cut into fixed chunks of kNormChunk elements, whatever the layer layout, so
+// every 16-byte load is aligned.  A chunk that lies inside one layer writes one partial
+// (head).  A chunk holding layer boundaries writes the part of the layer it starts in (head),
+// the part of the layer it ends in (tail) and finishes the layers that lie wholly inside it.
+__global__ __launch_bounds__(kThreads) void norm_chunks_kernel(
+    const float* __restrict__ g, int64_t N, const int64_t* __restrict__ off, int L,
+    double* __restrict__ head, double* __restrict__ tail, double* __restrict__ sumsq) {
+  __shared__ double red[kWaves];
+  const int64_t cs = (int64_t)blockIdx.x * kNormChunk;
+  const int64_t ce = min(N, cs + (int64_t)kNormChunk);
+  const int lf = layer_of(off, L, cs);
+  if (off[lf + 1] >= ce) {
+    double a0 = 0.0, a1 = 0.0;
+    if (ce - cs == kNormChunk) {
+      const float4* __restrict__ p = reinterpret_cast<const float4*>(g + cs);
+      float4 v[kNormIters];
+#pragma unroll
+      for (int i = 0; i < kNormIters; ++i) v[i] = p[threadIdx.x + i * kThreads];
+#pragma unroll
+      for (int i = 0; i < kNormIters; ++i) {
+        const double x = v[i].x, y = v[i].y, z = v[i].z, w = v[i].w;
+        a0 = fma(x, x, a0);
+        a1 = fma(y, y, a1);
+        a0 = fma(z, z, a0);
+        a1 = fma(w, w, a1);
+      }
+    } else {
+      for (int64_t i = cs + threadIdx.x; i < ce; i += kThreads) {
+        const double x = g[i];
+        a0 = fma(x, x, a0);
+      }
+    }
+    const double t = block_sum(a0 + a1, red);
+    if (threadIdx.x == 0) { head[blockIdx.x] = t; tail[blockIdx.x] = 0.0; }
+    return;
+  }
+  if (threadIdx.x == 0) tail[blockIdx.x] = 0.0;
+  for (int l = lf; l < L; ++l) {
+    const int64_t lo = off[l], hi = off[l + 1];
+    if (l > lf && lo >= ce) break;
+    const int64_t s = max(cs, lo), e = min(ce, hi);
+    double a = 0.0;
+    for (int64_t i = s + threadIdx.x; i < e; i += kThreads) {
+      const double x = g[i];
+      a = fma(x, x, a);
+    }
+    const double t = block_sum(a, red);
+    if (threadIdx.x == 0) {
+      if (l == lf) head[blockIdx.x] = t;
+      else if (hi >= ce) tail[blockIdx.x] = t;
+      else sumsq[l] = t;
+    }
+    if (hi >= ce) break;
+  }
+}
+
+// One workgroup per layer adds the partials of the chunks the layer touches, in chunk order
+// per thread and a fixed tree across threads.
+__global__ __launch_bounds__(kThreads) void norm_finish_kernel(
+    const int64_t* __restrict__ off, int64_t N, const double* __restrict__ head,
+    const double* __restrict__ tail, double* __restrict__ sumsq) {
+  __shared__ double red[kWaves];
+  const int l = blockIdx.x;
+  const int64_t s = off[l], e = off[l + 1];
+  if (e <= s || s < 0 || e > N) {
+    if (threadIdx.x == 0) sumsq[l] = 0.0;
+    return;
+  }
+  const int64_t b0 = s / kNormChunk, b1 = (e - 1) / kNormChunk;
+  const bool first = (s == b0 * kNormChunk);
+  if (b0 == b1) {
+    if (threadIdx.x == 0) {
+      if (first) sumsq[l] = head[b0];
+      else if (e == min(N, (b0 + 1) * (int64_t)kNormChunk)) sumsq[l] = tail[b0];
+      // otherwise the layer lies strictly inside chunk b0 and was finished there
+    }
+    return;
+  }
+  double a = 0.0;
+  for (int64_t b = b0 + 1 + threadIdx.x; b <= b1; b += kThreads) a += head[b];
+  const double t = block_sum(a, red);
+  if (threadIdx.x == 0) sumsq[l] = (first ? head[b0] : tail[b0]) + t;
+}
+
+// ------------------------------------------------------------------------------------------
+// selection
+// ------------------------------------------------------------------------------------------
+struct SegDesc {
+  uint32_t start;       // first element of the segment in g
+  uint32_t size;        // elements
+  uint32_t k;           // entries to select, 1 <= k <= size
+  uint32_t out_off;     // first output slot of the segment
+  uint32_t chunk_base;  // first chunk id of the segment
+};
+
+struct SegState {
+  uint32_t prefix;  // key bits fixed so far (right-aligned)
+  uint32_t k_rem;   // entries still to take inside the prefix bucket
+  uint32_t T;       // threshold key once resolved
+  uint32_t r;       // number of entries with key == T to take (lowest indices first)
+  uint32_t done;    // threshold resolved
+  uint32_t pad[3];
+};
+
+constexpr int kSegBatch = 192;
+struct SegBatch {
+  int32_t first;
+  int32_t count;
+  uint32_t total_chunks;  // written as the sentinel chunk_base of segment m by the last batch
+  int32_t m;
+  SegDesc d[kSegBatch];
+};
+static_assert(sizeof(SegBatch) <= 4000, "kernel argument block too large");
+
+constexpr int kBits0 = 11, kBits1 = 10, kBits2 = 10;
+constexpr int kHistBins = 1 << kBits0;  // bins reserved per segment (level 0 is the widest)
+
+__global__ void seg_setup_kernel(SegBatch b, SegDesc* __restrict__ seg, SegState* __restrict__ st) {
+  for (int i = threadIdx.x; i < b.count; i += blockDim.x) {
+    seg[b.first + i] = b.d[i];
+    SegState s;
+    s.prefix = 0; s.k_rem = b.d[i].k; s.T = 0; s.r = 0; s.done = 0;
+    s.pad[0] = s.pad[1] = s.pad[2] = 0;
+    st[b.first + i] = s;
+  }
+  if (threadIdx.x == 0 && b.first + b.count == b.m) {
+    SegDesc z; z.start = 0; z.size = 0; z.k = 0; z.out_off = 0; z.chunk_base = b.total_chunks;
+    seg[b.m] = z;
+  }
+}
+
+__global__ void zero_u32_kernel(uint32_t* __restrict__ p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x)
+    p[i] = 0u;
+}
+
+// Segment that owns chunk c: largest j in [0, m-1] with seg[j].chunk_base <= c.
+__device__ __forceinline__ int seg_of_chunk(const SegDesc* __restrict__ seg, int m, uint32_t c) {
+  int lo = 0, hi = m;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (seg[mid].chunk_base <= c) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// A chunk of a segment [s, e): chunk boundaries sit at multiples of 4 elements counted from
+// s rounded down to a multiple of 4, so 16-byte loads are aligned; elements outside [s, e) are
+// masked.  Wave w of the workgroup owns the w-th quarter of the chunk and lane `lane` loads
+// the 16-byte vector (i*64 + lane) of that quarter in step i, so index order inside a wave is
+// (step, lane, component).
+template <int ITERS>
+struct Chunk {
+  static constexpr int kElems = kThreads * 4 * ITERS;
+  uint32_t key[ITERS][4];
+  uint32_t raw[ITERS][4];
+  uint32_t valid[ITERS];  // 4-bit masks
+  int64_t base;           // absolute index of this thread's vector in step 0
+
+  __device__ __forceinline__ void load(const float* __restrict__ g, int64_t s, int64_t e,
+                                       uint32_t local_chunk) {
+    const int64_t a = s & ~int64_t(3);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    base = a + (int64_t)local_chunk * kElems + ((int64_t)wave * ITERS * 64 + lane) * 4;
+#pragma unroll
+    for (int i = 0; i < ITERS; ++i) {
+      const int64_t p = base + (int64_t)i * 256;
+      if (p >= s && p + 4 <= e) {
+        const uint4 v = *reinterpret_cast<const uint4*>(g + p);
+        raw[i][0] = v.x; raw[i][1] = v.y; raw[i][2] = v.z; raw[i][3] = v.w;
+        valid[i] = 0xF;
+      } else {
+        valid[i] = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const int64_t q = p + c;
+          raw[i][c] = 0;
+          if (q >= s && q < e) {
+            raw[i][c] = __float_as_uint(g[q]);
+            valid[i] |= 1u << c;
+          }
+        }
+      }
+#pragma unroll
+      for (int c = 0; c < 4; ++c) key[i][c] = raw[i][c] & 0x7FFFFFFFu;
+    }
+  }
+};
+
+__host__ __device__ inline uint32_t chunks_of(uint32_t start, uint32_t size, uint32_t chunk_elems) {
+  if (size == 0) return 0;
+  const uint64_t a = start & ~3u;
+  return (uint32_t)(((uint64_t)start + size - a + chunk_elems - 1) / chunk_elems);
+}
+
+// Digit histogram of one level.  Level 0 counts every element; deeper levels count only the
+// elements whose higher bits equal the prefix chosen so far.
+template <int ITERS, int LEVEL>
+__global__ __launch_bounds__(kThreads) void hist_kernel(const float* __restrict__ g,
+                                                        const SegDesc* __restrict__ seg,
+                                                        const SegState* __restrict__ st, int m,
+                                                        uint32_t* __restrict__ hist) {
+  constexpr int kBits = LEVEL == 0 ? kBits0 : (LEVEL == 1 ? kBits1 : kBits2);
+  constexpr int kShift = LEVEL == 0 ? (kBits1 + kBits2) : (LEVEL == 1 ? kBits2 : 0);
+  constexpr int kBins = 1 << kBits;
+  __shared__ uint32_t lh[kBins];
+  const int j = seg_of_chunk(seg, m, blockIdx.x);
+  if (LEVEL > 0 && st[j].done) return;
+  const SegDesc d = seg[j];
+  const uint32_t prefix = st[j].prefix;
+  for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
+  __syncthreads();
+  Chunk<ITERS> ch;
+  ch.load(g, d.start, (int64_t)d.start + d.size, blockIdx.x - d.chunk_base);
+#pragma unroll
+  for (int i = 0; i < ITERS; ++i) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const uint32_t key = ch.key[i][c];
+      bool on = (ch.valid[i] >> c) & 1u;
+      if (LEVEL > 0) on = on && ((key >> (kShift + kBits)) == prefix);
+      const uint32_t digit = (key >> kShift) & (kBins - 1);
+      if (LEVEL == 0) {
+        // Gradients cluster in few exponent buckets: let the lanes that share the first
+        // active lane's digit add once, the rest add individually.
+        const unsigned long long act = __ballot(on);
+        if (act) {
+          const int leader = __ffsll((long long)act) - 1;
+          const uint32_t dl = __shfl(digit, leader, 64);
+          const unsigned long long same = __ballot(on && digit == dl);
+          if (on) {
+            if (digit == dl) {
+              if ((int)(threadIdx.x & 63) == leader) atomicAdd(&lh[dl], (uint32_t)__popcll(same));
+            } else {
+              atomicAdd(&lh[digit], 1u);
+            }
+          }
+        }
+      } else {
+        if (on) atomicAdd(&lh[digit], 1u);
+      }
+    }
+  }
+  __syncthreads();
+  uint32_t* gh = hist + (size_t)j * kHistBins;
+  for (int b = threadIdx.x; b < kBins; b += kThreads) {
+    const uint32_t v = lh[b];
+    if (v) atomicAdd(&gh[b], v);
+  }
+}
+
+// One workgroup per segment: locate the bucket that holds the k_rem-th largest key of the
+// current prefix, extend the prefix by it, and clear the histogram for the next level.
+template <int LEVEL>
+__global__ __launch_bounds__(kThreads) void find_kernel(SegState* __restrict__ st,
+                                                        uint32_t* __restrict__ hist) {
+  constexpr int kBits = LEVEL == 0 ? kBits0 : (LEVEL == 1 ? kBits1 : kBits2);
+  constexpr int kRemBits = LEVEL == 0 ? (kBits1 + kBits2) : (LEVEL == 1 ? kBits2 : 0);
+  constexpr int kBins = 1 << kBits;
+  constexpr int kPer = kBins / kThreads;
+  __shared__ uint32_t wsum[kWaves];
+  const int j = blockIdx.x;
+  SegState s = st[j];
+  if (s.done) return;
+  uint32_t* gh = hist + (size_t)j * kHistBins;
+  // thread t owns the kPer bins just below kBins - t*kPer, i.e. threads walk the buckets from
+  // the largest keys down
+  const int top = kBins - threadIdx.x * kPer;
+  uint32_t v[kPer];
+  uint32_t mine = 0;
+#pragma unroll
+  for (int q = 0; q < kPer; ++q) {
+    v[q] = gh[top - 1 - q];
+    gh[top - 1 - q] = 0;
+    mine += v[q];
+  }
+  // exclusive prefix of `mine` over threads (ascending thread = descending key)
+  uint32_t inc = mine;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t n = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += n;
+  }
+  if (lane == 63) wsum[wave] = inc;
+  __syncthreads();
+  uint32_t before = inc - mine;
+  for (int w = 0; w < wave; ++w) before += wsum[w];
+  if (before < s.k_rem && s.k_rem <= before + mine) {
+    uint32_t above = before;
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) {
+      if (above < s.k_rem && s.k_rem <= above + v[q]) {
+        const uint32_t bin = (uint32_t)(top - 1 - q);
+        s.prefix = (s.prefix << kBits) | bin;
+        s.k_rem -= above;
+        if (kRemBits == 0) {
+          s.T = s.prefix;
+          s.r = s.k_rem;
+          s.done = 1;
+        } else if (v[q] == s.k_rem) {
+          // the whole bucket is taken: every key >= its lowest key is selected
+          s.T = s.prefix << kRemBits;
+          s.r = 0xFFFFFFFFu;
+          s.done = 1;
+        }
+        st[j] = s;
+        break;
+      }
+      above += v[q];
+    }
+  }
+}
+
+// Per chunk: how many keys exceed T and how many equal it.
+template <int ITERS>
+__global__ __launch_bounds__(kThreads) void count_kernel(const float* __restrict__ g,
+                                                         const SegDesc* __restrict__ seg,
+                                                         const SegState* __restrict__ st, int m,
+                                                         uint32_t* __restrict__ chunk_gt,
+                                                         uint32_t* __restrict__ chunk_eq) {
+  __shared__ uint32_t red[2 * kWaves];
+  const int j = seg_of_chunk(seg, m, blockIdx.x);
+  const SegDesc d = seg[j];
+  const uint32_t T = st[j].T;
+  Chunk<ITERS> ch;
+  ch.load(g, d.start, (int64_t)d.start + d.size, blockIdx.x - d.chunk_base);
+  uint32_t gt = 0, eq = 0;
+#pragma unroll
+  for (int i = 0; i < ITERS; ++i) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const bool on = (ch.valid[i] >> c) & 1u;
+      gt += (on && ch.key[i][c] > T) ? 1u : 0u;
+      eq += (on && ch.key[i][c] == T) ? 1u : 0u;
+    }
+  }
+  gt = wave_sum_u32(gt);
+  eq = wave_sum_u32(eq);
+  if ((threadIdx.x & 63) == 0) {
+    red[threadIdx.x >> 6] = gt;
+    red[kWaves + (threadIdx.x >> 6)] = eq;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    chunk_gt[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
+    chunk_eq[blockIdx.x] = red[kWaves] + red[kWaves + 1] + red[kWaves + 2] + red[kWaves + 3];
+  }
+}
+
+// One workgroup per segment walks the segment's chunks in order: eq_base = equal keys before
+// the chunk; out_base = output slot of the chunk's first selected entry.
+__global__ __launch_bounds__(kThreads) void scan_kernel(const SegDesc* __restrict__ seg,
+                                                        const SegState* __restrict__ st,
+                                                        const uint32_t* __restrict__ chunk_gt,
+                                                        const uint32_t* __restrict__ chunk_eq,
+                                                        uint32_t* __restrict__ out_base,
+                                                        uint32_t* __restrict__ eq_base) {
+  __shared__ uint32_t wsum[2][kWaves];
+  const int j = blockIdx.x;
+  const uint32_t c0 = seg[j].chunk_base, c1 = seg[j + 1].chunk_base;
+  const uint32_t r = st[j].r;
+  uint32_t carry_eq = 0, carry_out = seg[j].out_off;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (uint32_t t0 = c0; t0 < c1; t0 += kThreads) {
+    const uint32_t c = t0 + threadIdx.x;
+    const bool on = c < c1;
+    const uint32_t gt = on ? chunk_gt[c] : 0u;
+    const uint32_t eq = on ? chunk_eq[c] : 0u;
+    // inclusive scan of eq over the tile
+    uint32_t ie = eq;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t n = __shfl_up(ie, o, 64);
+      if (lane >= o) ie += n;
+    }
+    __syncthreads();
+    if (lane == 63) wsum[0][wave] = ie;
+    __syncthreads();
+    uint32_t eb = carry_eq + ie - eq;
+    for (int w = 0; w < wave; ++w) eb += wsum[0][w];
+    const uint32_t tile_eq = wsum[0][0] + wsum[0][1] + wsum[0][2] + wsum[0][3];
+    // ties taken from this chunk: those of rank below r
+    const uint32_t take = eb >= r ? 0u : min(eq, r - eb);
+    const uint32_t sel = gt + take;
+    uint32_t is = sel;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t n = __shfl_up(is, o, 64);
+      if (lane >= o) is += n;
+    }
+    if (lane == 63) wsum[1][wave] = is;
+    __syncthreads();
+    uint32_t ob = carry_out + is - sel;
+    for (int w = 0; w < wave; ++w) ob += wsum[1][w];
+    const uint32_t tile_sel = wsum[1][0] + wsum[1][1] + wsum[1][2] + wsum[1][3];
+    if (on) { out_base[c] = ob; eq_base[c] = eb; }
+    carry_eq += tile_eq;
+    carry_out += tile_sel;
+  }
+}
+
+// Exclusive prefix over the wavefront of a per-lane count in [0, 7], by three ballots.
+__device__ __forceinline__ uint32_t wave_excl_small(uint32_t cnt, uint32_t& total) {
+  const unsigned long long b0 = __ballot(cnt & 1u), b1 = __ballot(cnt & 2u), b2 = __ballot(cnt & 4u);
+  const int lane = threadIdx.x & 63;
+  const unsigned long long below = (1ull << lane) - 1ull;
+  total = (uint32_t)__popcll(b0) + 2u * (uint32_t)__popcll(b1) + 4u * (uint32_t)__popcll(b2);
+  return (uint32_t)__popcll(b0 & below) + 2u * (uint32_t)__popcll(b1 & below) +
+         4u * (uint32_t)__popcll(b2 & below);
+}
+
+// Ordered compaction of one chunk.
+template <int ITERS>
+__global__ __launch_bounds__(kThreads) void emit_kernel(
+    const float* __restrict__ g, const SegDesc* __restrict__ seg, const SegState* __restrict__ st,
+    int m, const uint32_t* __restrict__ chunk_eq, const uint32_t* __restrict__ out_base,
+    const uint32_t* __restrict__ eq_base, int32_t* __restrict__ idx_out,
+    float* __restrict__ val_out) {
+  __shared__ uint32_t wtot[2][kWaves];
+  const int j = seg_of_chunk(seg, m, blockIdx.x);
+  const SegDesc d = seg[j];
+  const uint32_t T = st[j].T, r = st[j].r;
+  const uint32_t eb = eq_base[blockIdx.x], ceq = chunk_eq[blockIdx.x];
+  // 0: none of the chunk's ties is taken, 1: all are, 2: the quota ends inside this chunk
+  const int mode = (eb >= r) ? 0 : ((r - eb >= ceq) ? 1 : 2);
+  Chunk<ITERS> ch;
+  ch.load(g, d.start, (int64_t)d.start + d.size, blockIdx.x - d.chunk_base);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+  uint32_t sel[ITERS];  // 4-bit masks of selected components
+  if (mode != 2) {
+#pragma unroll
+    for (int i = 0; i < ITERS; ++i) {
+      sel[i] = 0;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const bool on = (ch.valid[i] >> c) & 1u;
+        const bool s = mode == 1 ? ch.key[i][c] >= T : ch.key[i][c] > T;
+        sel[i] |= (on && s) ? (1u << c) : 0u;
+      }
+    }
+  } else {
+    // rank the ties of the chunk in index order: wave totals first, then in-wave prefixes
+    uint32_t eqm[ITERS];
+    uint32_t wave_eq = 0;
+#pragma unroll
+    for (int i = 0; i < ITERS; ++i) {
+      eqm[i] = 0;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const bool on = (ch.valid[i] >> c) & 1u;
+        eqm[i] |= (on && ch.key[i][c] == T) ? (1u << c) : 0u;
+      }
+      wave_eq += (uint32_t)__popc(eqm[i]);
+    }
+    wave_eq = wave_sum_u32(wave_eq);
+    if (lane == 0) wtot[1][wave] = wave_eq;
+    __syncthreads();
+    uint32_t rank = eb;
+    for (int w = 0; w < wave; ++w) rank += wtot[1][w];
+#pragma unroll
+    for (int i = 0; i < ITERS; ++i) {
+      uint32_t tot;
+      uint32_t mine = rank + wave_excl_small((uint32_t)__popc(eqm[i]), tot);
+      sel[i] = 0;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const bool on = (ch.valid[i] >> c) & 1u;
+        const bool is_eq = (eqm[i] >> c) & 1u;
+        bool s = on && ch.key[i][c] > T;
+        if (is_eq) { s = mine < r; ++mine; }
+        sel[i] |= s ? (1u << c) : 0u;
+      }
+      rank += tot;
+    }
+  }
+
+  uint32_t wave_sel = 0;
+#pragma unroll
+  for (int i = 0; i < ITERS; ++i) wave_sel += (uint32_t)__popc(sel[i]);
+  wave_sel = wave_sum_u32(wave_sel);
+  if (lane == 0) wtot[0][wave] = wave_sel;
+  __syncthreads();
+  uint32_t pos = out_base[blockIdx.x];
+  for (int w = 0; w < wave; ++w) pos += wtot[0][w];
+  if (wtot[0][wave] == 0) return;
+  const uint32_t lim = d.out_off + d.k;  // a segment never writes past its own k slots
+#pragma unroll
+  for (int i = 0; i < ITERS; ++i) {
+    if (__ballot(sel[i] != 0) == 0ull) continue;
+    uint32_t tot;
+    uint32_t mine = pos + wave_excl_small((uint32_t)__popc(sel[i]), tot);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      if (((sel[i] >> c) & 1u) && mine < lim) {
+        idx_out[mine] = (int32_t)(ch.base + (int64_t)i * 256 + c);
+        val_out[mine] = __uint_as_float(ch.raw[i][c]);
+        ++mine;
+      }
+    }
+    pos += tot;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// host drivers
+// ------------------------------------------------------------------------------------------
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+inline int chunk_iters_for(int64_t elems) { return elems > (int64_t(1) << 25) ? 16 : 4; }
+
+struct SelectLayout {
+  size_t seg, st, hist, cgt, ceq, obase, ebase, total;
+};
+
+SelectLayout select_layout(int64_t m, uint64_t chunks) {
+  SelectLayout w;
+  size_t o = 0;
+  w.seg = o;   o = align_up(o + sizeof(SegDesc) * (size_t)(m + 1), 256);
+  w.st = o;    o = align_up(o + sizeof(SegState) * (size_t)m, 256);
+  w.hist = o;  o = align_up(o + sizeof(uint32_t) * kHistBins * (size_t)m, 256);
+  w.cgt = o;   o = align_up(o + sizeof(uint32_t) * chunks, 256);
+  w.ceq = o;   o = align_up(o + sizeof(uint32_t) * chunks, 256);
+  w.obase = o; o = align_up(o + sizeof(uint32_t) * chunks, 256);
+  w.ebase = o; o = align_up(o + sizeof(uint32_t) * chunks, 256);
+  w.total = o;
+  return w;
+}
+
+// Upper bound on the chunk count of any set of m segments holding at most `elems` elements
+// (the chunk size depends on the total, so the bound covers both regimes).
+inline uint64_t max_chunks(int64_t elems, int64_t m) {
+  const int64_t small_cap = int64_t(1) << 25;
+  int64_t c = std::min(elems, small_cap) / (kThreads * 4 * 4);
+  if (elems > small_cap) c = std::max(c, elems / (kThreads * 4 * 16));
+  return (uint64_t)(c + 2 * m + 1);
+}
+
+#define HIP_TRY(x)                         \
+  do {                                     \
+    if ((x) != hipSuccess) return DEFT_EHIP; \
+  } while (0)
+
+template <int ITERS>
+int launch_select(const float* g, const SegDesc* seg, SegState* st, int m, uint32_t chunks,
+                  uint32_t* hist, uint32_t* cgt, uint32_t* ceq, uint32_t* obase, uint32_t* ebase,
+                  int32_t* idx_out, float* val_out, hipStream_t s) {
+  hist_kernel<ITERS, 0><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist);
+  find_kernel<0><<<m, kThreads, 0, s>>>(st, hist);
+  hist_kernel<ITERS, 1><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist);
+  find_kernel<1><<<m, kThreads, 0, s>>>(st, hist);
+  hist_kernel<ITERS, 2><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist);
+  find_kernel<2><<<m, kThreads, 0, s>>>(st, hist);
+  count_kernel<ITERS><<<chunks, kThreads, 0, s>>>(g, seg, st, m, cgt, ceq);
+  scan_kernel<<<m, kThreads, 0, s>>>(seg, st, cgt, ceq, obase, ebase);
+  emit_kernel<ITERS><<<chunks, kThreads, 0, s>>>(g, seg, st, m, ceq, obase, ebase, idx_out, val_out);
+  HIP_TRY(hipGetLastError());
+  return DEFT_OK;
+}
+
+// Enqueue the selection of `m` validated, non-empty segments (k >= 1 each).
+int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t share,
+               int32_t* idx_out, float* val_out, void* ws, size_t ws_bytes, hipStream_t s) {
+  const int m = (int)segs_in.size();
+  if (m == 0) return DEFT_OK;
+  const int iters = chunk_iters_for(share);
+  const uint32_t ce = (uint32_t)kThreads * 4 * iters;
+  std::vector<SegDesc> segs(segs_in);
+  uint64_t chunks = 0;
+  for (auto& d : segs) {
+    d.chunk_base = (uint32_t)chunks;
+    chunks += chunks_of(d.start, d.size, ce);
+  }
+  if (chunks > max_chunks(share, m) || chunks >= (uint64_t(1) << 31)) return DEFT_EWS;
+  const SelectLayout w = select_layout(m, chunks);
+  if (w.total > ws_bytes) return DEFT_EWS;
+  char* base = static_cast<char*>(ws);
+  SegDesc* seg = reinterpret_cast<SegDesc*>(base + w.seg);
+  SegState* st = reinterpret_cast<SegState*>(base + w.st);
+  uint32_t* hist = reinterpret_cast<uint32_t*>(base + w.hist);
+  for (int first = 0; first < m; first += kSegBatch) {
+    SegBatch b;
+    b.first = first;
+    b.count = std::min(kSegBatch, m - first);
+    b.total_chunks = (uint32_t)chunks;
+    b.m = m;
+    std::memcpy(b.d, segs.data() + first, sizeof(SegDesc) * (size_t)b.count);
+    seg_setup_kernel<<<1, kThreads, 0, s>>>(b, seg, st);
+  }
+  const size_t nh = (size_t)kHistBins * m;
+  zero_u32_kernel<<<(unsigned)std::min<size_t>((nh + kThreads - 1) / kThreads, 1024), kThreads, 0, s>>>(hist, nh);
+  uint32_t* cgt = reinterpret_cast<uint32_t*>(base + w.cgt);
+  uint32_t* ceq = reinterpret_cast<uint32_t*>(base + w.ceq);
+  uint32_t* ob = reinterpret_cast<uint32_t*>(base + w.obase);
+  uint32_t* eb = reinterpret_cast<uint32_t*>(base + w.ebase);
+  if (iters == 4)
+    return launch_select<4>(g, seg, st, m, (uint32_t)chunks, hist, cgt, ceq, ob, eb, idx_out, val_out, s);
+  return launch_select<16>(g, seg, st, m, (uint32_t)chunks, hist, cgt, ceq, ob, eb, idx_out, val_out, s);
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------
+// C ABI
+// ------------------------------------------------------------------------------------------
+extern "C" size_t deft_workspace_bytes(int op, int64_t elems, int32_t count) {
+  if (elems < 0 || count < 0) return 0;
+  switch (op) {
+    case DEFT_OP_NORMS: {
+      const size_t chunks = (size_t)((elems + kNormChunk - 1) / kNormChunk);
+      return align_up(2 * sizeof(double) * std::max<size_t>(chunks, 1), 256);
+    }
+    case DEFT_OP_SELECT:
+      return select_layout(std::max<int64_t>(count, 1), max_chunks(elems, count)).total;
+    case DEFT_OP_TOPK_GLOBAL:
+      return select_layout(1, max_chunks(elems, 1)).total;
+    default:
+      return 0;
+  }
+}
+
+extern "C" int deft_layer_norms(const float* g_dev, int64_t N, const int64_t* offsets_dev,
+                                int32_t L, double* sumsq_dev, void* ws_dev, size_t ws_bytes,
+                                void* stream) {
+  if (!g_dev || !offsets_dev || !sumsq_dev || !ws_dev || L < 1 || N < 1) return DEFT_EINVAL;
+  if (N > kMaxN) return DEFT_ERANGE;
+  if ((reinterpret_cast<uintptr_t>(g_dev) & 15u) || (reinterpret_cast<uintptr_t>(ws_dev) & 15u))
+    return DEFT_EINVAL;
+  if (ws_bytes < deft_workspace_bytes(DEFT_OP_NORMS, N, L)) return DEFT_EWS;
+  const unsigned chunks = (unsigned)((N + kNormChunk - 1) / kNormChunk);
+  double* head = static_cast<double*>(ws_dev);
+  double* tail = head + chunks;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  norm_chunks_kernel<<<chunks, kThreads, 0, s>>>(g_dev, N, offsets_dev, L, head, tail, sumsq_dev);
+  norm_finish_kernel<<<L, kThreads, 0, s>>>(offsets_dev, N, head, tail, sumsq_dev);
+  HIP_TRY(hipGetLastError());
+  return DEFT_OK;
+}
+
+extern "C" int deft_select(const float* g_dev, int64_t N, const int64_t* offsets_host,
+                           const int64_t* k_host, int32_t L, const int32_t* my_layers_host,
+                           int32_t my_count, int32_t* idx_out_dev, float* val_out_dev,
+                           int64_t* seg_off_host, int64_t out_cap, void* ws_dev, size_t ws_bytes,
+                           void* stream) {
+  if (!g_dev || !offsets_host || !k_host || !seg_off_host || my_count < 0 || out_cap < 0)
+    return DEFT_EINVAL;
+  if (my_count > 0 && !my_layers_host) return DEFT_EINVAL;
+  const int lay = deft_check_layout(offsets_host, L, N);
+  if (lay != DEFT_OK) return lay;
+  if (reinterpret_cast<uintptr_t>(g_dev) & 15u) return DEFT_EINVAL;
+  std::vector<SegDesc> segs;
+  segs.reserve(my_count);
+  std::vector<int64_t> seg_off(my_count + 1, 0);
+  int64_t share = 0, total_k = 0;
+  for (int32_t j = 0; j < my_count; ++j) {
+    const int32_t l = my_layers_host[j];
+    if (l < 0 || l >= L) return DEFT_EINVAL;
+    const int64_t size = offsets_host[l + 1] - offsets_host[l];
+    const int64_t k = k_host[l];
+    if (k < 0 || k > size) return DEFT_EINVAL;
+    if (k > 0) {
+      SegDesc d;
+      d.start = (uint32_t)offsets_host[l];
+      d.size = (uint32_t)size;
+      d.k = (uint32_t)k;
+      d.out_off = (uint32_t)total_k;
+      d.chunk_base = 0;
+      segs.push_back(d);
+      share += size;
+    }
+    total_k += k;
+    seg_off[j + 1] = total_k;
+    if (total_k > kMaxN) return DEFT_ERANGE;
+  }
+  if (total_k > out_cap) return DEFT_ECAP;
+  if (!segs.empty()) {
+    if (!idx_out_dev || !val_out_dev || !ws_dev) return DEFT_EINVAL;
+    if (reinterpret_cast<uintptr_t>(ws_dev) & 15u) return DEFT_EINVAL;
+    if (share > kMaxN) return DEFT_ERANGE;  // a layer listed more than once
+    if (ws_bytes < deft_workspace_bytes(DEFT_OP_SELECT, share, (int32_t)segs.size())) return DEFT_EWS;
+  }
+  const int rc = run_select(g_dev, segs, share, idx_out_dev, val_out_dev, ws_dev, ws_bytes,
+                            static_cast<hipStream_t>(stream));
+  if (rc != DEFT_OK) return rc;
+  std::copy(seg_off.begin(), seg_off.end(), seg_off_host);
+  return DEFT_OK;
+}
+
+extern "C" int topk_global(const float* g_dev, int64_t N, int64_t K, int32_t* idx_out_dev,
+                           float* val_out_dev, void* ws_dev, size_t ws_bytes, void* stream) {
+  if (!g_dev || N < 1 || K < 0 || K > N) return DEFT_EINVAL;
+  if (N > kMaxN) return DEFT_ERANGE;
+  if (reinterpret_cast<uintptr_t>(g_dev) & 15u) return DEFT_EINVAL;
+  if (K == 0) return DEFT_OK;
+  if (!idx_out_dev || !val_out_dev || !ws_dev) return DEFT_EINVAL;
+  if (reinterpret_cast<uintptr_t>(ws_dev) & 15u) return DEFT_EINVAL;
+  if (ws_bytes < deft_workspace_bytes(DEFT_OP_TOPK_GLOBAL, N, 1)) return DEFT_EWS;
+  std::vector<SegDesc> segs(1);
+  segs[0].start = 0;
+  segs[0].size = (uint32_t)N;
+  segs[0].k = (uint32_t)K;
+  segs[0].out_off = 0;
+  segs[0].chunk_base = 0;
+  return run_select(g_dev, segs, N, idx_out_dev, val_out_dev, ws_dev, ws_bytes,
+                    static_cast<hipStream_t>(stream));
+}
