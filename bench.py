@@ -93,18 +93,18 @@ def main():
     plan_ms = []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    h = stream.cuda_stream
     for s in range(args.steps):
         e = ev[s]
         e[0].record(stream)
-        B.deft_layer_norms(g, sel.offsets_dev, sel.sumsq_host, sel.ws)
+        sel.enqueue_norms(g, h)
         e[1].record(stream)
         stream.synchronize()
         p0 = time.perf_counter()
-        norms = B.deft_norms_from_sumsq(sel.sumsq_host.numpy())
-        k, owner, mine = sel.plan(norms, rank, 0)
+        cnt = sel.plan_host(rank, 0)
         p1 = time.perf_counter()
         e[2].record(stream)
-        seg = B.deft_select(g, sel.offsets, k, mine, sel.idx_out, sel.val_out, sel.ws)
+        k_r = sel.enqueue_select(g, cnt, h)
         e[3].record(stream)
         stream.synchronize()
         plan_ms.append((p1 - p0) * 1e3)
@@ -114,8 +114,8 @@ def main():
     norm_ms = [e[0].elapsed_time(e[1]) for e in ev]
     select_ms = [e[2].elapsed_time(e[3]) for e in ev]
 
+    k, owner, mine = sel.k_h.copy(), sel.owner_h.copy(), sel.mine_h[:cnt].copy()
     S_r = int(sel.sizes[mine].sum())
-    k_r = int(seg[-1])
     deft_bytes = 4 * N + 4 * S_r + 8 * k_r
     value = deft_bytes / (ms_per_step * 1e-3) / 1e9
 

@@ -102,10 +102,14 @@ extern "C" int deft_alloc_k(const double* norms, const int64_t* sizes, int32_t L
     if (sizes[l] < 1) return DEFT_EINVAL;
     if (!(norms[l] >= 0.0) || !std::isfinite(norms[l])) return DEFT_EINVAL;
   }
+  // priority order: norm descending, position ascending among equal norms
+  std::vector<std::pair<double, int32_t>> keyed(L);
+  for (int32_t l = 0; l < L; ++l) keyed[l] = {norms[l], l};
+  std::sort(keyed.begin(), keyed.end(), [](const auto& a, const auto& b) {
+    return a.first > b.first || (a.first == b.first && a.second < b.second);
+  });
   std::vector<int32_t> order(L);
-  std::iota(order.begin(), order.end(), 0);
-  std::stable_sort(order.begin(), order.end(),
-                   [&](int32_t a, int32_t b) { return norms[a] > norms[b]; });
+  for (int32_t j = 0; j < L; ++j) order[j] = keyed[j].second;
   std::vector<double> norm_remain(L);
   double acc = 0.0;
   for (int32_t j = L - 1; j >= 0; --j) {
@@ -139,7 +143,8 @@ bool check_sizes_k(const int64_t* sizes, const int64_t* k, int32_t L) {
 
 // Alg. 4.  The listing rescans the cost list for its maximum and the bin loads for their
 // minimum at every step, taking the first occurrence of each; the same choices are made here
-// by visiting the layers once in (cost descending, position ascending) order.
+// by visiting the layers once in (cost descending, position ascending) order and keeping the
+// bins in a heap ordered by (load, id).  ln(1) is exactly 0, so k = 1 layers skip the call.
 extern "C" int deft_assign_layers(const int64_t* sizes, const int64_t* k, int32_t L,
                                   int32_t n_workers, int64_t iteration, int32_t rank,
                                   int32_t* owner_bin, int32_t* my_layers, int32_t* my_count) {
@@ -148,22 +153,37 @@ extern "C" int deft_assign_layers(const int64_t* sizes, const int64_t* k, int32_
   if (!check_sizes_k(sizes, k, L)) return DEFT_EINVAL;
   const int32_t cycle = (int32_t)(iteration % n_workers);
   const int32_t curr_part = (cycle + rank) % n_workers;
-  std::vector<double> cost(L);
-  for (int32_t l = 0; l < L; ++l) cost[l] = (double)sizes[l] * std::log((double)k[l]);
-  std::vector<int32_t> order(L);
-  std::iota(order.begin(), order.end(), 0);
-  std::stable_sort(order.begin(), order.end(),
-                   [&](int32_t a, int32_t b) { return cost[a] > cost[b]; });
-  std::vector<double> size_bin(n_workers, 0.0);
+  // layers in (cost descending, position ascending) order
+  std::vector<std::pair<double, int32_t>> item(L);
+  for (int32_t l = 0; l < L; ++l)
+    item[l] = {k[l] == 1 ? 0.0 : (double)sizes[l] * std::log((double)k[l]), l};
+  std::sort(item.begin(), item.end(), [](const auto& a, const auto& b) {
+    return a.first > b.first || (a.first == b.first && a.second < b.second);
+  });
+  // bins as a binary min-heap on (load, id): its top is the first bin of minimal load
+  std::vector<std::pair<double, int32_t>> heap(n_workers);
+  for (int32_t b = 0; b < n_workers; ++b) heap[b] = {0.0, b};  // already a valid heap
+  const auto lighter = [](const std::pair<double, int32_t>& a, const std::pair<double, int32_t>& b) {
+    return a.first < b.first || (a.first == b.first && a.second < b.second);
+  };
   int32_t cnt = 0;
   for (int32_t j = 0; j < L; ++j) {
-    const int32_t idx_max = order[j];
-    int32_t bin_min = 0;
-    for (int32_t b = 1; b < n_workers; ++b)
-      if (size_bin[b] < size_bin[bin_min]) bin_min = b;
+    const int32_t idx_max = item[j].second;
+    const int32_t bin_min = heap[0].second;
     owner_bin[idx_max] = bin_min;
-    size_bin[bin_min] = size_bin[bin_min] + cost[idx_max];
     if (bin_min == curr_part) my_layers[cnt++] = idx_max;
+    heap[0].first = heap[0].first + item[j].first;
+    // sift the grown bin down
+    int32_t i = 0;
+    for (;;) {
+      const int32_t a = 2 * i + 1, b = a + 1;
+      int32_t best = i;
+      if (a < n_workers && lighter(heap[a], heap[best])) best = a;
+      if (b < n_workers && lighter(heap[b], heap[best])) best = b;
+      if (best == i) break;
+      std::swap(heap[i], heap[best]);
+      i = best;
+    }
   }
   *my_count = cnt;
   return DEFT_OK;

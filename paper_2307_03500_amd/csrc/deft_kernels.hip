@@ -54,7 +54,13 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
 // ------------------------------------------------------------------------------------------
 // norm pass (Sec. 4.2): sumsq[l] = sum over layer l of g^2, fp64
 // ------------------------------------------------------------------------------------------
-constexpr int kNormIters = 8;                              // 16-byte loads per thread
+#ifndef DEFT_NORM_ITERS
+#define DEFT_NORM_ITERS 4
+#endif
+#ifndef DEFT_HIST0_MODE
+#define DEFT_HIST0_MODE 0
+#endif
+constexpr int kNormIters = DEFT_NORM_ITERS;                // 16-byte loads per thread
 constexpr int kNormChunk = kThreads * 4 * kNormIters;      // elements per workgroup
 
 // Largest l in [0, L-1] with off[l] <= x (off[0] == 0 <= x).
@@ -71,11 +77,17 @@ __device__ __forceinline__ int layer_of(const int64_t* __restrict__ off, int L, 
 // every 16-byte load is aligned.  A chunk that lies inside one layer writes one partial
 // (head).  A chunk holding layer boundaries writes the part of the layer it starts in (head),
 // the part of the layer it ends in (tail) and finishes the layers that lie wholly inside it.
-__global__ __launch_bounds__(kThreads) void norm_chunks_kernel(
+#ifndef DEFT_NORM_MODE
+#define DEFT_NORM_MODE 0
+#endif
+#ifndef DEFT_NORM_GRID
+#define DEFT_NORM_GRID 0
+#endif
+__device__ __forceinline__ void norm_one_chunk(
     const float* __restrict__ g, int64_t N, const int64_t* __restrict__ off, int L,
-    double* __restrict__ head, double* __restrict__ tail, double* __restrict__ sumsq) {
-  __shared__ double red[kWaves];
-  const int64_t cs = (int64_t)blockIdx.x * kNormChunk;
+    double* __restrict__ head, double* __restrict__ tail, double* __restrict__ sumsq,
+    int64_t chunk, double* red) {
+  const int64_t cs = chunk * kNormChunk;
   const int64_t ce = min(N, cs + (int64_t)kNormChunk);
   const int lf = layer_of(off, L, cs);
   if (off[lf + 1] >= ce) {
@@ -84,7 +96,18 @@ __global__ __launch_bounds__(kThreads) void norm_chunks_kernel(
       const float4* __restrict__ p = reinterpret_cast<const float4*>(g + cs);
       float4 v[kNormIters];
 #pragma unroll
+#if DEFT_NORM_MODE == 2
+      for (int i = 0; i < kNormIters; ++i) v[i] = __builtin_nontemporal_load(&p[threadIdx.x + i * kThreads]);
+#else
       for (int i = 0; i < kNormIters; ++i) v[i] = p[threadIdx.x + i * kThreads];
+#endif
+#if DEFT_NORM_MODE == 1
+      float f = 0.f;
+#pragma unroll
+      for (int i = 0; i < kNormIters; ++i) f += v[i].x + v[i].y + v[i].z + v[i].w;
+      if (f == 1.2345f) head[chunk] = f;
+      return;
+#endif
 #pragma unroll
       for (int i = 0; i < kNormIters; ++i) {
         const double x = v[i].x, y = v[i].y, z = v[i].z, w = v[i].w;
@@ -100,10 +123,10 @@ __global__ __launch_bounds__(kThreads) void norm_chunks_kernel(
       }
     }
     const double t = block_sum(a0 + a1, red);
-    if (threadIdx.x == 0) { head[blockIdx.x] = t; tail[blockIdx.x] = 0.0; }
+    if (threadIdx.x == 0) { head[chunk] = t; tail[chunk] = 0.0; }
     return;
   }
-  if (threadIdx.x == 0) tail[blockIdx.x] = 0.0;
+  if (threadIdx.x == 0) tail[chunk] = 0.0;
   for (int l = lf; l < L; ++l) {
     const int64_t lo = off[l], hi = off[l + 1];
     if (l > lf && lo >= ce) break;
@@ -115,12 +138,21 @@ __global__ __launch_bounds__(kThreads) void norm_chunks_kernel(
     }
     const double t = block_sum(a, red);
     if (threadIdx.x == 0) {
-      if (l == lf) head[blockIdx.x] = t;
-      else if (hi >= ce) tail[blockIdx.x] = t;
+      if (l == lf) head[chunk] = t;
+      else if (hi >= ce) tail[chunk] = t;
       else sumsq[l] = t;
     }
     if (hi >= ce) break;
   }
+}
+
+__global__ __launch_bounds__(kThreads) void norm_chunks_kernel(
+    const float* __restrict__ g, int64_t N, const int64_t* __restrict__ off, int L,
+    double* __restrict__ head, double* __restrict__ tail, double* __restrict__ sumsq,
+    int64_t n_chunks) {
+  __shared__ double red[kWaves];
+  for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x)
+    norm_one_chunk(g, N, off, L, head, tail, sumsq, c, red);
 }
 
 // One workgroup per layer adds the partials of the chunks the layer touches, in chunk order
@@ -159,7 +191,8 @@ struct SegDesc {
   uint32_t size;        // elements
   uint32_t k;           // entries to select, 1 <= k <= size
   uint32_t out_off;     // first output slot of the segment
-  uint32_t chunk_base;  // first chunk id of the segment
+  uint32_t chunk_base;  // first chunk id of the segment in the count/emit passes
+  uint32_t hchunk_base; // first chunk id of the segment in the histogram passes (larger chunks)
 };
 
 struct SegState {
@@ -171,12 +204,14 @@ struct SegState {
   uint32_t pad[3];
 };
 
-constexpr int kSegBatch = 192;
+constexpr int kSegBatch = 160;
 struct SegBatch {
   int32_t first;
   int32_t count;
   uint32_t total_chunks;  // written as the sentinel chunk_base of segment m by the last batch
+  uint32_t total_hchunks;
   int32_t m;
+  int32_t pad;
   SegDesc d[kSegBatch];
 };
 static_assert(sizeof(SegBatch) <= 4000, "kernel argument block too large");
@@ -184,8 +219,19 @@ static_assert(sizeof(SegBatch) <= 4000, "kernel argument block too large");
 constexpr int kBits0 = 11, kBits1 = 10, kBits2 = 10;
 constexpr int kHistBins = 1 << kBits0;  // bins reserved per segment (level 0 is the widest)
 
-__global__ void seg_setup_kernel(SegBatch b, SegDesc* __restrict__ seg, SegState* __restrict__ st) {
-  for (int i = threadIdx.x; i < b.count; i += blockDim.x) {
+// Writes one batch of segment descriptors (passed as kernel arguments) and their initial
+// state; the first batch also clears the histograms.
+__global__ __launch_bounds__(kThreads) void seg_setup_kernel(SegBatch b, SegDesc* __restrict__ seg,
+                                                             SegState* __restrict__ st,
+                                                             uint32_t* __restrict__ zero_from,
+                                                             size_t zero_count) {
+  if (b.first == 0) {
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < zero_count;
+         i += (size_t)gridDim.x * kThreads)
+      zero_from[i] = 0u;
+  }
+  if (blockIdx.x != 0) return;
+  for (int i = threadIdx.x; i < b.count; i += kThreads) {
     seg[b.first + i] = b.d[i];
     SegState s;
     s.prefix = 0; s.k_rem = b.d[i].k; s.T = 0; s.r = 0; s.done = 0;
@@ -194,14 +240,9 @@ __global__ void seg_setup_kernel(SegBatch b, SegDesc* __restrict__ seg, SegState
   }
   if (threadIdx.x == 0 && b.first + b.count == b.m) {
     SegDesc z; z.start = 0; z.size = 0; z.k = 0; z.out_off = 0; z.chunk_base = b.total_chunks;
+    z.hchunk_base = b.total_hchunks;
     seg[b.m] = z;
   }
-}
-
-__global__ void zero_u32_kernel(uint32_t* __restrict__ p, size_t n) {
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
-       i += (size_t)gridDim.x * blockDim.x)
-    p[i] = 0u;
 }
 
 // Segment that owns chunk c: largest j in [0, m-1] with seg[j].chunk_base <= c.
@@ -210,6 +251,15 @@ __device__ __forceinline__ int seg_of_chunk(const SegDesc* __restrict__ seg, int
   while (hi - lo > 1) {
     const int mid = (lo + hi) >> 1;
     if (seg[mid].chunk_base <= c) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+__device__ __forceinline__ int seg_of_hchunk(const SegDesc* __restrict__ seg, int m, uint32_t c) {
+  int lo = 0, hi = m;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (seg[mid].hchunk_base <= c) lo = mid; else hi = mid;
   }
   return lo;
 }
@@ -231,26 +281,41 @@ struct Chunk {
                                        uint32_t local_chunk) {
     const int64_t a = s & ~int64_t(3);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    base = a + (int64_t)local_chunk * kElems + ((int64_t)wave * ITERS * 64 + lane) * 4;
+    const int64_t cstart = a + (int64_t)local_chunk * kElems;
+    base = cstart + ((int64_t)wave * ITERS * 64 + lane) * 4;
+    if (cstart >= s && cstart + kElems <= e) {
+      // interior chunk (uniform over the workgroup): all loads in flight together
+      const uint4* __restrict__ p = reinterpret_cast<const uint4*>(g + base);
 #pragma unroll
-    for (int i = 0; i < ITERS; ++i) {
-      const int64_t p = base + (int64_t)i * 256;
-      if (p >= s && p + 4 <= e) {
-        const uint4 v = *reinterpret_cast<const uint4*>(g + p);
+      for (int i = 0; i < ITERS; ++i) {
+        const uint4 v = p[i * 64];
         raw[i][0] = v.x; raw[i][1] = v.y; raw[i][2] = v.z; raw[i][3] = v.w;
         valid[i] = 0xF;
-      } else {
-        valid[i] = 0;
+      }
+    } else {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const int64_t q = p + c;
-          raw[i][c] = 0;
-          if (q >= s && q < e) {
-            raw[i][c] = __float_as_uint(g[q]);
-            valid[i] |= 1u << c;
+      for (int i = 0; i < ITERS; ++i) {
+        const int64_t p = base + (int64_t)i * 256;
+        if (p >= s && p + 4 <= e) {
+          const uint4 v = *reinterpret_cast<const uint4*>(g + p);
+          raw[i][0] = v.x; raw[i][1] = v.y; raw[i][2] = v.z; raw[i][3] = v.w;
+          valid[i] = 0xF;
+        } else {
+          valid[i] = 0;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const int64_t q = p + c;
+            raw[i][c] = 0;
+            if (q >= s && q < e) {
+              raw[i][c] = __float_as_uint(g[q]);
+              valid[i] |= 1u << c;
+            }
           }
         }
       }
+    }
+#pragma unroll
+    for (int i = 0; i < ITERS; ++i) {
 #pragma unroll
       for (int c = 0; c < 4; ++c) key[i][c] = raw[i][c] & 0x7FFFFFFFu;
     }
@@ -263,76 +328,16 @@ __host__ __device__ inline uint32_t chunks_of(uint32_t start, uint32_t size, uin
   return (uint32_t)(((uint64_t)start + size - a + chunk_elems - 1) / chunk_elems);
 }
 
-// Digit histogram of one level.  Level 0 counts every element; deeper levels count only the
-// elements whose higher bits equal the prefix chosen so far.
-template <int ITERS, int LEVEL>
-__global__ __launch_bounds__(kThreads) void hist_kernel(const float* __restrict__ g,
-                                                        const SegDesc* __restrict__ seg,
-                                                        const SegState* __restrict__ st, int m,
-                                                        uint32_t* __restrict__ hist) {
-  constexpr int kBits = LEVEL == 0 ? kBits0 : (LEVEL == 1 ? kBits1 : kBits2);
-  constexpr int kShift = LEVEL == 0 ? (kBits1 + kBits2) : (LEVEL == 1 ? kBits2 : 0);
-  constexpr int kBins = 1 << kBits;
-  __shared__ uint32_t lh[kBins];
-  const int j = seg_of_chunk(seg, m, blockIdx.x);
-  if (LEVEL > 0 && st[j].done) return;
-  const SegDesc d = seg[j];
-  const uint32_t prefix = st[j].prefix;
-  for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
-  __syncthreads();
-  Chunk<ITERS> ch;
-  ch.load(g, d.start, (int64_t)d.start + d.size, blockIdx.x - d.chunk_base);
-#pragma unroll
-  for (int i = 0; i < ITERS; ++i) {
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const uint32_t key = ch.key[i][c];
-      bool on = (ch.valid[i] >> c) & 1u;
-      if (LEVEL > 0) on = on && ((key >> (kShift + kBits)) == prefix);
-      const uint32_t digit = (key >> kShift) & (kBins - 1);
-      if (LEVEL == 0) {
-        // Gradients cluster in few exponent buckets: let the lanes that share the first
-        // active lane's digit add once, the rest add individually.
-        const unsigned long long act = __ballot(on);
-        if (act) {
-          const int leader = __ffsll((long long)act) - 1;
-          const uint32_t dl = __shfl(digit, leader, 64);
-          const unsigned long long same = __ballot(on && digit == dl);
-          if (on) {
-            if (digit == dl) {
-              if ((int)(threadIdx.x & 63) == leader) atomicAdd(&lh[dl], (uint32_t)__popcll(same));
-            } else {
-              atomicAdd(&lh[digit], 1u);
-            }
-          }
-        }
-      } else {
-        if (on) atomicAdd(&lh[digit], 1u);
-      }
-    }
-  }
-  __syncthreads();
-  uint32_t* gh = hist + (size_t)j * kHistBins;
-  for (int b = threadIdx.x; b < kBins; b += kThreads) {
-    const uint32_t v = lh[b];
-    if (v) atomicAdd(&gh[b], v);
-  }
-}
-
-// One workgroup per segment: locate the bucket that holds the k_rem-th largest key of the
+// Run by one whole workgroup: locate the bucket that holds the k_rem-th largest key of the
 // current prefix, extend the prefix by it, and clear the histogram for the next level.
 template <int LEVEL>
-__global__ __launch_bounds__(kThreads) void find_kernel(SegState* __restrict__ st,
-                                                        uint32_t* __restrict__ hist) {
+__device__ __forceinline__ void find_bucket(SegState* __restrict__ st, uint32_t* __restrict__ gh,
+                                            int j, uint32_t* __restrict__ wsum) {
   constexpr int kBits = LEVEL == 0 ? kBits0 : (LEVEL == 1 ? kBits1 : kBits2);
   constexpr int kRemBits = LEVEL == 0 ? (kBits1 + kBits2) : (LEVEL == 1 ? kBits2 : 0);
   constexpr int kBins = 1 << kBits;
   constexpr int kPer = kBins / kThreads;
-  __shared__ uint32_t wsum[kWaves];
-  const int j = blockIdx.x;
   SegState s = st[j];
-  if (s.done) return;
-  uint32_t* gh = hist + (size_t)j * kHistBins;
   // thread t owns the kPer bins just below kBins - t*kPer, i.e. threads walk the buckets from
   // the largest keys down
   const int top = kBins - threadIdx.x * kPer;
@@ -352,6 +357,7 @@ __global__ __launch_bounds__(kThreads) void find_kernel(SegState* __restrict__ s
     const uint32_t n = __shfl_up(inc, o, 64);
     if (lane >= o) inc += n;
   }
+  __syncthreads();
   if (lane == 63) wsum[wave] = inc;
   __syncthreads();
   uint32_t before = inc - mine;
@@ -379,6 +385,147 @@ __global__ __launch_bounds__(kThreads) void find_kernel(SegState* __restrict__ s
       }
       above += v[q];
     }
+  }
+}
+
+// Digit histogram of one level.  Level 0 counts every element; deeper levels count only the
+// elements whose higher bits equal the prefix chosen so far.
+template <int ITERS, int LEVEL>
+__global__ __launch_bounds__(kThreads) void hist_kernel(const float* __restrict__ g,
+                                                        const SegDesc* __restrict__ seg,
+                                                        const SegState* __restrict__ st, int m,
+                                                        uint32_t* __restrict__ hist) {
+  constexpr int kBits = LEVEL == 0 ? kBits0 : (LEVEL == 1 ? kBits1 : kBits2);
+  constexpr int kShift = LEVEL == 0 ? (kBits1 + kBits2) : (LEVEL == 1 ? kBits2 : 0);
+  constexpr int kBins = 1 << kBits;
+  constexpr int kRep = (LEVEL == 0 && DEFT_HIST0_MODE == 2) ? 4 : 1;  // copies of each bin
+  __shared__ uint32_t lh[kBins * kRep];
+  const int j = seg_of_hchunk(seg, m, blockIdx.x);
+  if (LEVEL > 0 && st[j].done) return;
+  const SegDesc d = seg[j];
+  const uint32_t prefix = st[j].prefix;
+  for (int b = threadIdx.x; b < kBins * kRep; b += kThreads) lh[b] = 0;
+  __syncthreads();
+  Chunk<ITERS> ch;
+  ch.load(g, d.start, (int64_t)d.start + d.size, blockIdx.x - d.hchunk_base);
+#pragma unroll
+  for (int i = 0; i < ITERS; ++i) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const uint32_t key = ch.key[i][c];
+      bool on = (ch.valid[i] >> c) & 1u;
+      if (LEVEL > 0) on = on && ((key >> (kShift + kBits)) == prefix);
+      const uint32_t digit = (key >> kShift) & (kBins - 1);
+      if (LEVEL == 0 && DEFT_HIST0_MODE == 0) {
+        // Gradients cluster in few exponent buckets: let the lanes that share the first
+        // active lane's digit add once, the rest add individually.
+        const unsigned long long act = __ballot(on);
+        if (act) {
+          const int leader = __ffsll((long long)act) - 1;
+          const uint32_t dl = (uint32_t)__builtin_amdgcn_readlane((int)digit, leader);
+          const unsigned long long same = __ballot(on && digit == dl);
+          if (on) {
+            if (digit == dl) {
+              if ((int)(threadIdx.x & 63) == leader) atomicAdd(&lh[dl], (uint32_t)__popcll(same));
+            } else {
+              atomicAdd(&lh[digit], 1u);
+            }
+          }
+        }
+      } else {
+        if (on) atomicAdd(&lh[digit * kRep + (threadIdx.x & (kRep - 1))], 1u);
+      }
+    }
+  }
+  __syncthreads();
+  uint32_t* gh = hist + (size_t)j * kHistBins;
+  for (int b = threadIdx.x; b < kBins; b += kThreads) {
+    uint32_t v = 0;
+#pragma unroll
+    for (int c = 0; c < kRep; ++c) v += lh[b * kRep + c];
+    if (v) atomicAdd(&gh[b], v);
+  }
+}
+
+// One workgroup per segment turns the finished histogram into the next prefix.  (Doing this in
+// the histogram kernel's last-finishing workgroup was measured slower: each workgroup then ends
+// with a device-scope round trip, which costs more than a kernel boundary.)
+template <int LEVEL>
+__global__ __launch_bounds__(kThreads) void find_kernel(SegState* __restrict__ st,
+                                                        uint32_t* __restrict__ hist) {
+  __shared__ uint32_t wsum[kWaves];
+  const int j = blockIdx.x;
+  if (st[j].done) return;
+  find_bucket<LEVEL>(st, hist + (size_t)j * kHistBins, j, wsum);
+}
+
+// Run by one whole workgroup: walks the chunks of segment j
+// in order.  eq_base = equal keys before the chunk; out_base = output slot of the chunk's
+// first selected entry.  Each thread handles kScanPer consecutive chunks per round.
+constexpr int kScanPer = 32;
+__device__ __forceinline__ void scan_segment(const SegDesc* __restrict__ seg,
+                                             const SegState* __restrict__ st, int j,
+                                             const uint32_t* __restrict__ chunk_gt,
+                                             const uint32_t* __restrict__ chunk_eq,
+                                             uint32_t* __restrict__ out_base,
+                                             uint32_t* __restrict__ eq_base,
+                                             uint32_t* __restrict__ wsum /* 2*kWaves */) {
+  const uint32_t c0 = seg[j].chunk_base, c1 = seg[j + 1].chunk_base;
+  const uint32_t r = st[j].r;
+  uint32_t carry_eq = 0, carry_out = seg[j].out_off;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (uint32_t t0 = c0; t0 < c1; t0 += kThreads * kScanPer) {
+    const uint32_t base = t0 + threadIdx.x * kScanPer;
+    uint32_t gt[kScanPer], eq[kScanPer];
+    uint32_t se = 0;
+#pragma unroll
+    for (int q = 0; q < kScanPer; ++q) {
+      const bool on = base + q < c1;
+      gt[q] = on ? chunk_gt[base + q] : 0u;
+      eq[q] = on ? chunk_eq[base + q] : 0u;
+      se += eq[q];
+    }
+    uint32_t ie = se;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t n = __shfl_up(ie, o, 64);
+      if (lane >= o) ie += n;
+    }
+    __syncthreads();
+    if (lane == 63) wsum[wave] = ie;
+    __syncthreads();
+    uint32_t eb = carry_eq + ie - se;
+    for (int w = 0; w < wave; ++w) eb += wsum[w];
+    const uint32_t tile_eq = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+    uint32_t ebq[kScanPer], sel[kScanPer];
+    uint32_t ss = 0;
+#pragma unroll
+    for (int q = 0; q < kScanPer; ++q) {
+      ebq[q] = eb;
+      // ties taken from this chunk: those of rank below r
+      const uint32_t take = eb >= r ? 0u : min(eq[q], r - eb);
+      sel[q] = gt[q] + take;
+      ss += sel[q];
+      eb += eq[q];
+    }
+    uint32_t is = ss;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t n = __shfl_up(is, o, 64);
+      if (lane >= o) is += n;
+    }
+    if (lane == 63) wsum[kWaves + wave] = is;
+    __syncthreads();
+    uint32_t ob = carry_out + is - ss;
+    for (int w = 0; w < wave; ++w) ob += wsum[kWaves + w];
+    const uint32_t tile_sel = wsum[kWaves] + wsum[kWaves + 1] + wsum[kWaves + 2] + wsum[kWaves + 3];
+#pragma unroll
+    for (int q = 0; q < kScanPer; ++q) {
+      if (base + q < c1) { out_base[base + q] = ob; eq_base[base + q] = ebq[q]; }
+      ob += sel[q];
+    }
+    carry_eq += tile_eq;
+    carry_out += tile_sel;
   }
 }
 
@@ -418,56 +565,15 @@ __global__ __launch_bounds__(kThreads) void count_kernel(const float* __restrict
   }
 }
 
-// One workgroup per segment walks the segment's chunks in order: eq_base = equal keys before
-// the chunk; out_base = output slot of the chunk's first selected entry.
+// One workgroup per segment: chunk counts -> output positions.
 __global__ __launch_bounds__(kThreads) void scan_kernel(const SegDesc* __restrict__ seg,
                                                         const SegState* __restrict__ st,
                                                         const uint32_t* __restrict__ chunk_gt,
                                                         const uint32_t* __restrict__ chunk_eq,
                                                         uint32_t* __restrict__ out_base,
                                                         uint32_t* __restrict__ eq_base) {
-  __shared__ uint32_t wsum[2][kWaves];
-  const int j = blockIdx.x;
-  const uint32_t c0 = seg[j].chunk_base, c1 = seg[j + 1].chunk_base;
-  const uint32_t r = st[j].r;
-  uint32_t carry_eq = 0, carry_out = seg[j].out_off;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (uint32_t t0 = c0; t0 < c1; t0 += kThreads) {
-    const uint32_t c = t0 + threadIdx.x;
-    const bool on = c < c1;
-    const uint32_t gt = on ? chunk_gt[c] : 0u;
-    const uint32_t eq = on ? chunk_eq[c] : 0u;
-    // inclusive scan of eq over the tile
-    uint32_t ie = eq;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const uint32_t n = __shfl_up(ie, o, 64);
-      if (lane >= o) ie += n;
-    }
-    __syncthreads();
-    if (lane == 63) wsum[0][wave] = ie;
-    __syncthreads();
-    uint32_t eb = carry_eq + ie - eq;
-    for (int w = 0; w < wave; ++w) eb += wsum[0][w];
-    const uint32_t tile_eq = wsum[0][0] + wsum[0][1] + wsum[0][2] + wsum[0][3];
-    // ties taken from this chunk: those of rank below r
-    const uint32_t take = eb >= r ? 0u : min(eq, r - eb);
-    const uint32_t sel = gt + take;
-    uint32_t is = sel;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const uint32_t n = __shfl_up(is, o, 64);
-      if (lane >= o) is += n;
-    }
-    if (lane == 63) wsum[1][wave] = is;
-    __syncthreads();
-    uint32_t ob = carry_out + is - sel;
-    for (int w = 0; w < wave; ++w) ob += wsum[1][w];
-    const uint32_t tile_sel = wsum[1][0] + wsum[1][1] + wsum[1][2] + wsum[1][3];
-    if (on) { out_base[c] = ob; eq_base[c] = eb; }
-    carry_eq += tile_eq;
-    carry_out += tile_sel;
-  }
+  __shared__ uint32_t wsum[2 * kWaves];
+  scan_segment(seg, st, blockIdx.x, chunk_gt, chunk_eq, out_base, eq_base, wsum);
 }
 
 // Exclusive prefix over the wavefront of a per-lane count in [0, 7], by three ballots.
@@ -578,7 +684,21 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(
 // ------------------------------------------------------------------------------------------
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-inline int chunk_iters_for(int64_t elems) { return elems > (int64_t(1) << 25) ? 16 : 4; }
+#ifndef DEFT_SEL_ITERS_SMALL
+#define DEFT_SEL_ITERS_SMALL 4
+#endif
+#ifndef DEFT_SEL_ITERS_LARGE
+#define DEFT_SEL_ITERS_LARGE 8
+#endif
+#ifndef DEFT_HIST_ITERS_SMALL
+#define DEFT_HIST_ITERS_SMALL 16
+#endif
+#ifndef DEFT_HIST_ITERS_LARGE
+#define DEFT_HIST_ITERS_LARGE 32
+#endif
+inline int chunk_iters_for(int64_t elems) {
+  return elems > (int64_t(1) << 25) ? DEFT_SEL_ITERS_LARGE : DEFT_SEL_ITERS_SMALL;
+}
 
 struct SelectLayout {
   size_t seg, st, hist, cgt, ceq, obase, ebase, total;
@@ -602,8 +722,8 @@ SelectLayout select_layout(int64_t m, uint64_t chunks) {
 // (the chunk size depends on the total, so the bound covers both regimes).
 inline uint64_t max_chunks(int64_t elems, int64_t m) {
   const int64_t small_cap = int64_t(1) << 25;
-  int64_t c = std::min(elems, small_cap) / (kThreads * 4 * 4);
-  if (elems > small_cap) c = std::max(c, elems / (kThreads * 4 * 16));
+  int64_t c = std::min(elems, small_cap) / (kThreads * 4 * DEFT_SEL_ITERS_SMALL);
+  if (elems > small_cap) c = std::max(c, elems / (kThreads * 4 * DEFT_SEL_ITERS_LARGE));
   return (uint64_t)(c + 2 * m + 1);
 }
 
@@ -612,15 +732,19 @@ inline uint64_t max_chunks(int64_t elems, int64_t m) {
     if ((x) != hipSuccess) return DEFT_EHIP; \
   } while (0)
 
-template <int ITERS>
+// The histogram passes walk larger chunks (HITERS) than the count/emit passes (ITERS): a
+// histogram workgroup ends by merging up to 2048 bins into the segment's histogram with global
+// atomics, a fixed cost that wants amortising; count/emit have no such tail and balance better
+// with small chunks.
+template <int ITERS, int HITERS>
 int launch_select(const float* g, const SegDesc* seg, SegState* st, int m, uint32_t chunks,
-                  uint32_t* hist, uint32_t* cgt, uint32_t* ceq, uint32_t* obase, uint32_t* ebase,
-                  int32_t* idx_out, float* val_out, hipStream_t s) {
-  hist_kernel<ITERS, 0><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist);
+                  uint32_t hchunks, uint32_t* hist, uint32_t* cgt, uint32_t* ceq, uint32_t* obase,
+                  uint32_t* ebase, int32_t* idx_out, float* val_out, hipStream_t s) {
+  hist_kernel<HITERS, 0><<<hchunks, kThreads, 0, s>>>(g, seg, st, m, hist);
   find_kernel<0><<<m, kThreads, 0, s>>>(st, hist);
-  hist_kernel<ITERS, 1><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist);
+  hist_kernel<HITERS, 1><<<hchunks, kThreads, 0, s>>>(g, seg, st, m, hist);
   find_kernel<1><<<m, kThreads, 0, s>>>(st, hist);
-  hist_kernel<ITERS, 2><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist);
+  hist_kernel<HITERS, 2><<<hchunks, kThreads, 0, s>>>(g, seg, st, m, hist);
   find_kernel<2><<<m, kThreads, 0, s>>>(st, hist);
   count_kernel<ITERS><<<chunks, kThreads, 0, s>>>(g, seg, st, m, cgt, ceq);
   scan_kernel<<<m, kThreads, 0, s>>>(seg, st, cgt, ceq, obase, ebase);
@@ -635,12 +759,16 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   const int m = (int)segs_in.size();
   if (m == 0) return DEFT_OK;
   const int iters = chunk_iters_for(share);
+  const bool small = iters == DEFT_SEL_ITERS_SMALL;
   const uint32_t ce = (uint32_t)kThreads * 4 * iters;
+  const uint32_t hce = (uint32_t)kThreads * 4 * (small ? DEFT_HIST_ITERS_SMALL : DEFT_HIST_ITERS_LARGE);
   std::vector<SegDesc> segs(segs_in);
-  uint64_t chunks = 0;
+  uint64_t chunks = 0, hchunks = 0;
   for (auto& d : segs) {
     d.chunk_base = (uint32_t)chunks;
+    d.hchunk_base = (uint32_t)hchunks;
     chunks += chunks_of(d.start, d.size, ce);
+    hchunks += chunks_of(d.start, d.size, hce);
   }
   if (chunks > max_chunks(share, m) || chunks >= (uint64_t(1) << 31)) return DEFT_EWS;
   const SelectLayout w = select_layout(m, chunks);
@@ -649,24 +777,28 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   SegDesc* seg = reinterpret_cast<SegDesc*>(base + w.seg);
   SegState* st = reinterpret_cast<SegState*>(base + w.st);
   uint32_t* hist = reinterpret_cast<uint32_t*>(base + w.hist);
+  const size_t nzero = (size_t)kHistBins * m;
+  const unsigned setup_blocks = (unsigned)std::min<size_t>((nzero + 4 * kThreads - 1) / (4 * kThreads), 256);
   for (int first = 0; first < m; first += kSegBatch) {
     SegBatch b;
     b.first = first;
     b.count = std::min(kSegBatch, m - first);
     b.total_chunks = (uint32_t)chunks;
+    b.total_hchunks = (uint32_t)hchunks;
     b.m = m;
+    b.pad = 0;
     std::memcpy(b.d, segs.data() + first, sizeof(SegDesc) * (size_t)b.count);
-    seg_setup_kernel<<<1, kThreads, 0, s>>>(b, seg, st);
+    seg_setup_kernel<<<first == 0 ? setup_blocks : 1, kThreads, 0, s>>>(b, seg, st, hist, nzero);
   }
-  const size_t nh = (size_t)kHistBins * m;
-  zero_u32_kernel<<<(unsigned)std::min<size_t>((nh + kThreads - 1) / kThreads, 1024), kThreads, 0, s>>>(hist, nh);
   uint32_t* cgt = reinterpret_cast<uint32_t*>(base + w.cgt);
   uint32_t* ceq = reinterpret_cast<uint32_t*>(base + w.ceq);
   uint32_t* ob = reinterpret_cast<uint32_t*>(base + w.obase);
   uint32_t* eb = reinterpret_cast<uint32_t*>(base + w.ebase);
-  if (iters == 4)
-    return launch_select<4>(g, seg, st, m, (uint32_t)chunks, hist, cgt, ceq, ob, eb, idx_out, val_out, s);
-  return launch_select<16>(g, seg, st, m, (uint32_t)chunks, hist, cgt, ceq, ob, eb, idx_out, val_out, s);
+  if (small)
+    return launch_select<DEFT_SEL_ITERS_SMALL, DEFT_HIST_ITERS_SMALL>(
+        g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, idx_out, val_out, s);
+  return launch_select<DEFT_SEL_ITERS_LARGE, DEFT_HIST_ITERS_LARGE>(
+      g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, idx_out, val_out, s);
 }
 
 }  // namespace
@@ -702,7 +834,8 @@ extern "C" int deft_layer_norms(const float* g_dev, int64_t N, const int64_t* of
   double* head = static_cast<double*>(ws_dev);
   double* tail = head + chunks;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  norm_chunks_kernel<<<chunks, kThreads, 0, s>>>(g_dev, N, offsets_dev, L, head, tail, sumsq_dev);
+  const unsigned grid = DEFT_NORM_GRID > 0 ? std::min<unsigned>(chunks, DEFT_NORM_GRID) : chunks;
+  norm_chunks_kernel<<<grid, kThreads, 0, s>>>(g_dev, N, offsets_dev, L, head, tail, sumsq_dev, chunks);
   norm_finish_kernel<<<L, kThreads, 0, s>>>(offsets_dev, N, head, tail, sumsq_dev);
   HIP_TRY(hipGetLastError());
   return DEFT_OK;
@@ -736,6 +869,7 @@ extern "C" int deft_select(const float* g_dev, int64_t N, const int64_t* offsets
       d.k = (uint32_t)k;
       d.out_off = (uint32_t)total_k;
       d.chunk_base = 0;
+      d.hchunk_base = 0;
       segs.push_back(d);
       share += size;
     }
@@ -772,6 +906,7 @@ extern "C" int topk_global(const float* g_dev, int64_t N, int64_t K, int32_t* id
   segs[0].k = (uint32_t)K;
   segs[0].out_off = 0;
   segs[0].chunk_base = 0;
+  segs[0].hchunk_base = 0;
   return run_select(g_dev, segs, N, idx_out_dev, val_out_dev, ws_dev, ws_bytes,
                     static_cast<hipStream_t>(stream));
 }

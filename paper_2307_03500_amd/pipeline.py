@@ -3,7 +3,8 @@
 This class only owns buffers and orders the calls; it computes nothing itself:
   deft_partition (once) -> deft_layer_norms [device] -> stream sync ->
   deft_norms_from_sumsq -> deft_alloc_k -> deft_assign_layers [host] -> deft_select [device].
-torch supplies device memory, pinned host memory and the stream.
+torch supplies device memory, pinned host memory and the stream.  All host arrays are
+allocated once and their addresses cached, so a call costs a few ctypes invocations.
 """
 from __future__ import annotations
 
@@ -24,8 +25,8 @@ class Selection:
     owner_bin: np.ndarray   # bin of each layer (host)
     my_layers: np.ndarray   # this worker's layers, in placement order (host)
     seg_off: np.ndarray     # output segment offsets (host)
-    idx_dev: torch.Tensor   # int32 [k_r] global indices, device
-    val_dev: torch.Tensor   # float32 [k_r] values, device
+    idx_dev: torch.Tensor   # int32 [k_r] global indices, device (view of the selector's buffer)
+    val_dev: torch.Tensor   # float32 [k_r] values, device (view of the selector's buffer)
     times: dict = field(default_factory=dict)
 
     @property
@@ -44,46 +45,98 @@ class DeftSelector:
         self.n = int(n_workers)
         self.d = float(d)
         self.offsets, self.layer_tensor = B.deft_partition(tensor_sizes, n_workers)
-        self.L = len(self.offsets) - 1
+        self.L = L = len(self.offsets) - 1
         self.N = int(self.offsets[-1])
         self.sizes = np.diff(self.offsets).astype(np.int64)
         self.K = int(np.floor(self.N * self.d + 0.5))
         dev = self.device
         self.offsets_dev = torch.from_numpy(self.offsets).to(dev)
-        self.sumsq_host = torch.zeros(self.L, dtype=torch.float64).pin_memory()
-        nb = max(B.deft_workspace_bytes(B.OP_NORMS, self.N, self.L),
-                 B.deft_workspace_bytes(B.OP_SELECT, self.N, self.L),
+        self.sumsq_host = torch.zeros(L, dtype=torch.float64).pin_memory()
+        nb = max(B.deft_workspace_bytes(B.OP_NORMS, self.N, L),
+                 B.deft_workspace_bytes(B.OP_SELECT, self.N, L),
                  B.deft_workspace_bytes(B.OP_TOPK_GLOBAL, self.N, 1))
         self.ws = torch.empty(nb, dtype=torch.uint8, device=dev)
         # sum of k_l can exceed K by the number of layers clamped up to 1 (Alg. 3)
-        self.out_cap = int(out_cap) if out_cap is not None else self.K + self.L + 1
-        self.idx_out = torch.empty(max(self.out_cap, self.K, 1), dtype=torch.int32, device=dev)
-        self.val_out = torch.empty(max(self.out_cap, self.K, 1), dtype=torch.float32, device=dev)
+        self.out_cap = int(out_cap) if out_cap is not None else self.K + L + 1
+        cap = max(self.out_cap, self.K, 1)
+        self.idx_out = torch.empty(cap, dtype=torch.int32, device=dev)
+        self.val_out = torch.empty(cap, dtype=torch.float32, device=dev)
+        # persistent host arrays of the plan
+        self.norms_h = np.zeros(L, np.float64)
+        self.k_h = np.zeros(L, np.int64)
+        self.owner_h = np.zeros(L, np.int32)
+        self.mine_h = np.zeros(L, np.int32)
+        self.cnt_h = np.zeros(1, np.int32)
+        self.seg_h = np.zeros(L + 1, np.int64)
+        # cached addresses
+        self._lib = B.lib()
+        self._p = {
+            "off_dev": self.offsets_dev.data_ptr(), "sumsq": self.sumsq_host.data_ptr(),
+            "ws": self.ws.data_ptr(), "ws_bytes": nb, "idx": self.idx_out.data_ptr(),
+            "val": self.val_out.data_ptr(), "off": self.offsets.ctypes.data,
+            "sizes": self.sizes.ctypes.data, "norms": self.norms_h.ctypes.data,
+            "k": self.k_h.ctypes.data, "owner": self.owner_h.ctypes.data,
+            "mine": self.mine_h.ctypes.data, "cnt": self.cnt_h.ctypes.data,
+            "seg": self.seg_h.ctypes.data,
+        }
+        self._cap = cap
 
-    # -- steps ----------------------------------------------------------------------------
+    # -- steps (each is one or a few C-ABI calls on cached addresses) ----------------------
+    def enqueue_norms(self, g: torch.Tensor, stream_handle: int) -> None:
+        p = self._p
+        rc = self._lib.deft_layer_norms(g.data_ptr(), self.N, p["off_dev"], self.L, p["sumsq"],
+                                        p["ws"], p["ws_bytes"], stream_handle)
+        if rc:
+            raise B.DeftError(rc, "deft_layer_norms")
+
+    def plan_host(self, rank: int, iteration: int) -> int:
+        """sumsq (already on the host) -> norms -> k -> bins; returns this rank's layer count."""
+        p, lib, L = self._p, self._lib, self.L
+        rc = lib.deft_norms_from_sumsq(p["sumsq"], L, p["norms"])
+        if rc:
+            raise B.DeftError(rc, "deft_norms_from_sumsq")
+        rc = lib.deft_alloc_k(p["norms"], p["sizes"], L, self.N, self.d, p["k"])
+        if rc:
+            raise B.DeftError(rc, "deft_alloc_k")
+        rc = lib.deft_assign_layers(p["sizes"], p["k"], L, self.n, iteration, rank, p["owner"],
+                                    p["mine"], p["cnt"])
+        if rc:
+            raise B.DeftError(rc, "deft_assign_layers")
+        return int(self.cnt_h[0])
+
+    def enqueue_select(self, g: torch.Tensor, count: int, stream_handle: int) -> int:
+        """Alg. 5 on the planned layers; returns k_r."""
+        p = self._p
+        rc = self._lib.deft_select(g.data_ptr(), self.N, p["off"], p["k"], self.L, p["mine"], count,
+                                   p["idx"], p["val"], p["seg"], self._cap, p["ws"], p["ws_bytes"],
+                                   stream_handle)
+        if rc:
+            raise B.DeftError(rc, "deft_select")
+        return int(self.seg_h[count])
+
+    # -- convenience wrappers ---------------------------------------------------------------
     def norms(self, g: torch.Tensor) -> np.ndarray:
-        B.deft_layer_norms(g, self.offsets_dev, self.sumsq_host, self.ws)
-        torch.cuda.current_stream().synchronize()
+        st = torch.cuda.current_stream()
+        self.enqueue_norms(g, st.cuda_stream)
+        st.synchronize()
         return B.deft_norms_from_sumsq(self.sumsq_host.numpy())
 
-    def plan(self, norms: np.ndarray, rank: int, iteration: int):
-        k = B.deft_alloc_k(norms, self.sizes, self.N, self.d)
-        owner, mine = B.deft_assign_layers(self.sizes, k, self.n, iteration, rank)
-        return k, owner, mine
-
-    def select(self, g: torch.Tensor, rank: int, iteration: int = 0, timed: bool = False) -> Selection:
+    def select(self, g: torch.Tensor, rank: int, iteration: int = 0) -> Selection:
         assert g.dtype == torch.float32 and g.numel() == self.N and g.device == self.device
+        st = torch.cuda.current_stream()
+        h = st.cuda_stream
         t0 = time.perf_counter()
-        norms = self.norms(g)
+        self.enqueue_norms(g, h)
+        st.synchronize()
         t1 = time.perf_counter()
-        k, owner, mine = self.plan(norms, rank, iteration)
+        cnt = self.plan_host(rank, iteration)
         t2 = time.perf_counter()
-        seg = B.deft_select(g, self.offsets, k, mine, self.idx_out, self.val_out, self.ws)
-        if timed:
-            torch.cuda.current_stream().synchronize()
+        kr = self.enqueue_select(g, cnt, h)
+        st.synchronize()
         t3 = time.perf_counter()
-        kr = int(seg[-1])
-        return Selection(norms, k, owner, mine, seg, self.idx_out[:kr], self.val_out[:kr],
+        return Selection(self.norms_h.copy(), self.k_h.copy(), self.owner_h.copy(),
+                         self.mine_h[:cnt].copy(), self.seg_h[:cnt + 1].copy(),
+                         self.idx_out[:kr], self.val_out[:kr],
                          {"norm_ms": (t1 - t0) * 1e3, "plan_ms": (t2 - t1) * 1e3,
                           "select_ms": (t3 - t2) * 1e3})
 
