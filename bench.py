@@ -57,6 +57,9 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all-ranks", action="store_true", help="also time Alg. 5 on every rank")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one device-to-device copy of the vector (4N read + 4N written), "
+                         "the known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU (one worker's share of an n-worker job); "
@@ -79,6 +82,12 @@ def main():
     g = torch.from_numpy(gs.g).to(dev)
     N, L, n, rank = gs.N, sel.L, gs.n_workers, args.rank
     stream = torch.cuda.current_stream()
+
+    if args.calibrate_copy:
+        g2 = torch.empty_like(g)
+        g2.copy_(g)
+        torch.cuda.synchronize()
+        del g2
 
     def step():
         return sel.select(g, rank=rank, iteration=0)

@@ -11,7 +11,7 @@ the paper's order and notation.  The selection steps (Alg. 5 and the conventiona
 Sec. 1 / 3.1) have a plain definition -- sort by magnitude, keep the first k -- and the
 oracle is that definition.
 
-Readings taken where the paper is silent (all restated in the design notes of the repo):
+Readings taken where the paper is silent:
   * norm = L2 norm, plain (not squared)                               (Sec. 4.2; Sec. 2 uses L2)
   * k = n_g * d is rounded half-up to an integer:  K = floor(N*d + 0.5)      (Alg. 3, first step)
   * priority = norm descending, ties by layer position ascending             (Sec. 4.2)
