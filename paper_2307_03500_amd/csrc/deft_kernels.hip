@@ -57,9 +57,6 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
 #ifndef DEFT_NORM_ITERS
 #define DEFT_NORM_ITERS 4
 #endif
-#ifndef DEFT_HIST0_MODE
-#define DEFT_HIST0_MODE 0
-#endif
 constexpr int kNormIters = DEFT_NORM_ITERS;                // 16-byte loads per thread
 constexpr int kNormChunk = kThreads * 4 * kNormIters;      // elements per workgroup
 
@@ -217,7 +214,6 @@ struct SegBatch {
 static_assert(sizeof(SegBatch) <= 4000, "kernel argument block too large");
 
 constexpr int kBits0 = 11, kBits1 = 10, kBits2 = 10;
-constexpr int kHistBins = 1 << kBits0;  // bins reserved per segment (level 0 is the widest)
 
 // Writes one batch of segment descriptors (passed as kernel arguments) and their initial
 // state; the first batch also clears the histograms.
@@ -328,16 +324,23 @@ __host__ __device__ inline uint32_t chunks_of(uint32_t start, uint32_t size, uin
   return (uint32_t)(((uint64_t)start + size - a + chunk_elems - 1) / chunk_elems);
 }
 
-// Run by one whole workgroup: locate the bucket that holds the k_rem-th largest key of the
-// current prefix, extend the prefix by it, and clear the histogram for the next level.
+// Histogram storage of one segment: level 0, 1, 2 one after the other.
+constexpr int kHistStride = (1 << kBits0) + (1 << kBits1) + (1 << kBits2);
+__host__ __device__ constexpr int hist_offset(int level) {
+  return level == 0 ? 0 : (level == 1 ? (1 << kBits0) : (1 << kBits0) + (1 << kBits1));
+}
+
+// Run by one whole workgroup: from the finished histogram `gh` of level LEVEL and the state
+// `s` before that level, locate the bucket holding the k_rem-th largest key of the current
+// prefix and return the state after the level (in every thread).  If the bucket is taken
+// entirely, or this was the last level, the threshold is resolved.
 template <int LEVEL>
-__device__ __forceinline__ void find_bucket(SegState* __restrict__ st, uint32_t* __restrict__ gh,
-                                            int j, uint32_t* __restrict__ wsum) {
+__device__ __forceinline__ SegState find_bucket(const uint32_t* __restrict__ gh, SegState s,
+                                                uint32_t* __restrict__ lds /* kWaves + 8 words */) {
   constexpr int kBits = LEVEL == 0 ? kBits0 : (LEVEL == 1 ? kBits1 : kBits2);
   constexpr int kRemBits = LEVEL == 0 ? (kBits1 + kBits2) : (LEVEL == 1 ? kBits2 : 0);
   constexpr int kBins = 1 << kBits;
   constexpr int kPer = kBins / kThreads;
-  SegState s = st[j];
   // thread t owns the kPer bins just below kBins - t*kPer, i.e. threads walk the buckets from
   // the largest keys down
   const int top = kBins - threadIdx.x * kPer;
@@ -346,7 +349,6 @@ __device__ __forceinline__ void find_bucket(SegState* __restrict__ st, uint32_t*
 #pragma unroll
   for (int q = 0; q < kPer; ++q) {
     v[q] = gh[top - 1 - q];
-    gh[top - 1 - q] = 0;
     mine += v[q];
   }
   // exclusive prefix of `mine` over threads (ascending thread = descending key)
@@ -358,56 +360,90 @@ __device__ __forceinline__ void find_bucket(SegState* __restrict__ st, uint32_t*
     if (lane >= o) inc += n;
   }
   __syncthreads();
-  if (lane == 63) wsum[wave] = inc;
+  if (lane == 63) lds[wave] = inc;
+  if (threadIdx.x == 0) {
+    // result if no bucket qualifies (cannot happen while the histogram holds >= k_rem keys):
+    // a threshold above every key, i.e. select nothing
+    lds[kWaves + 0] = s.prefix; lds[kWaves + 1] = s.k_rem; lds[kWaves + 2] = 0x80000000u;
+    lds[kWaves + 3] = 0u; lds[kWaves + 4] = 1u;
+  }
   __syncthreads();
   uint32_t before = inc - mine;
-  for (int w = 0; w < wave; ++w) before += wsum[w];
+  for (int w = 0; w < wave; ++w) before += lds[w];
   if (before < s.k_rem && s.k_rem <= before + mine) {
     uint32_t above = before;
 #pragma unroll
     for (int q = 0; q < kPer; ++q) {
       if (above < s.k_rem && s.k_rem <= above + v[q]) {
         const uint32_t bin = (uint32_t)(top - 1 - q);
-        s.prefix = (s.prefix << kBits) | bin;
-        s.k_rem -= above;
+        SegState o = s;
+        o.prefix = (s.prefix << kBits) | bin;
+        o.k_rem = s.k_rem - above;
         if (kRemBits == 0) {
-          s.T = s.prefix;
-          s.r = s.k_rem;
-          s.done = 1;
-        } else if (v[q] == s.k_rem) {
+          o.T = o.prefix;
+          o.r = o.k_rem;
+          o.done = 1;
+        } else if (v[q] == o.k_rem) {
           // the whole bucket is taken: every key >= its lowest key is selected
-          s.T = s.prefix << kRemBits;
-          s.r = 0xFFFFFFFFu;
-          s.done = 1;
+          o.T = o.prefix << kRemBits;
+          o.r = 0xFFFFFFFFu;
+          o.done = 1;
         }
-        st[j] = s;
+        lds[kWaves + 0] = o.prefix; lds[kWaves + 1] = o.k_rem; lds[kWaves + 2] = o.T;
+        lds[kWaves + 3] = o.r; lds[kWaves + 4] = o.done;
         break;
       }
       above += v[q];
     }
   }
+  __syncthreads();
+  SegState o = s;
+  o.prefix = lds[kWaves + 0]; o.k_rem = lds[kWaves + 1]; o.T = lds[kWaves + 2];
+  o.r = lds[kWaves + 3]; o.done = lds[kWaves + 4];
+  return o;
+}
+
+// State hand-over between the passes.  st[v] (v = 0..3) is the state after v digit levels;
+// each pass reads st[LEVEL], and -- when FUSED -- first derives st[LEVEL] itself from
+// st[LEVEL-1] and the previous level's histogram (every workgroup repeats that small scan; the
+// segment's first workgroup records it for the later passes).  When not FUSED a separate
+// one-workgroup-per-segment kernel did it.  The fused form drops three dependent launches,
+// which is what bounds short segments; long vectors keep the separate kernels because
+// re-reading the histogram in every workgroup would add ~10 % traffic there.
+template <int LEVEL_DONE, bool FUSED>
+__device__ __forceinline__ SegState state_after(SegState* __restrict__ st, int m, int j,
+                                                const uint32_t* __restrict__ hist, bool first_block,
+                                                uint32_t* __restrict__ lds) {
+  if (!FUSED || LEVEL_DONE == 0) return st[(size_t)LEVEL_DONE * m + j];
+  SegState s = st[(size_t)(LEVEL_DONE - 1) * m + j];
+  if (!s.done)
+    s = find_bucket<LEVEL_DONE - 1>(hist + (size_t)j * kHistStride + hist_offset(LEVEL_DONE - 1), s, lds);
+  if (first_block && threadIdx.x == 0) st[(size_t)LEVEL_DONE * m + j] = s;
+  return s;
 }
 
 // Digit histogram of one level.  Level 0 counts every element; deeper levels count only the
 // elements whose higher bits equal the prefix chosen so far.
-template <int ITERS, int LEVEL>
+template <int ITERS, int LEVEL, bool FUSED>
 __global__ __launch_bounds__(kThreads) void hist_kernel(const float* __restrict__ g,
                                                         const SegDesc* __restrict__ seg,
-                                                        const SegState* __restrict__ st, int m,
+                                                        SegState* __restrict__ st, int m,
                                                         uint32_t* __restrict__ hist) {
   constexpr int kBits = LEVEL == 0 ? kBits0 : (LEVEL == 1 ? kBits1 : kBits2);
   constexpr int kShift = LEVEL == 0 ? (kBits1 + kBits2) : (LEVEL == 1 ? kBits2 : 0);
   constexpr int kBins = 1 << kBits;
-  constexpr int kRep = (LEVEL == 0 && DEFT_HIST0_MODE == 2) ? 4 : 1;  // copies of each bin
-  __shared__ uint32_t lh[kBins * kRep];
+  __shared__ uint32_t lh[kBins];
+  __shared__ uint32_t fl[kWaves + 8];
   const int j = seg_of_hchunk(seg, m, blockIdx.x);
-  if (LEVEL > 0 && st[j].done) return;
   const SegDesc d = seg[j];
-  const uint32_t prefix = st[j].prefix;
-  for (int b = threadIdx.x; b < kBins * kRep; b += kThreads) lh[b] = 0;
+  const uint32_t local = blockIdx.x - d.hchunk_base;
+  const SegState s = state_after<LEVEL, FUSED>(st, m, j, hist, local == 0, fl);
+  if (s.done) return;
+  const uint32_t prefix = s.prefix;
+  for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
   __syncthreads();
   Chunk<ITERS> ch;
-  ch.load(g, d.start, (int64_t)d.start + d.size, blockIdx.x - d.hchunk_base);
+  ch.load(g, d.start, (int64_t)d.start + d.size, local);
 #pragma unroll
   for (int i = 0; i < ITERS; ++i) {
 #pragma unroll
@@ -416,7 +452,7 @@ __global__ __launch_bounds__(kThreads) void hist_kernel(const float* __restrict_
       bool on = (ch.valid[i] >> c) & 1u;
       if (LEVEL > 0) on = on && ((key >> (kShift + kBits)) == prefix);
       const uint32_t digit = (key >> kShift) & (kBins - 1);
-      if (LEVEL == 0 && DEFT_HIST0_MODE == 0) {
+      if (LEVEL == 0) {
         // Gradients cluster in few exponent buckets: let the lanes that share the first
         // active lane's digit add once, the rest add individually.
         const unsigned long long act = __ballot(on);
@@ -433,30 +469,28 @@ __global__ __launch_bounds__(kThreads) void hist_kernel(const float* __restrict_
           }
         }
       } else {
-        if (on) atomicAdd(&lh[digit * kRep + (threadIdx.x & (kRep - 1))], 1u);
+        if (on) atomicAdd(&lh[digit], 1u);
       }
     }
   }
   __syncthreads();
-  uint32_t* gh = hist + (size_t)j * kHistBins;
+  uint32_t* gh = hist + (size_t)j * kHistStride + hist_offset(LEVEL);
   for (int b = threadIdx.x; b < kBins; b += kThreads) {
-    uint32_t v = 0;
-#pragma unroll
-    for (int c = 0; c < kRep; ++c) v += lh[b * kRep + c];
+    const uint32_t v = lh[b];
     if (v) atomicAdd(&gh[b], v);
   }
 }
 
-// One workgroup per segment turns the finished histogram into the next prefix.  (Doing this in
-// the histogram kernel's last-finishing workgroup was measured slower: each workgroup then ends
-// with a device-scope round trip, which costs more than a kernel boundary.)
+// One workgroup per segment: st[LEVEL+1] from st[LEVEL] and the level's histogram (the
+// unfused form of the hand-over).
 template <int LEVEL>
-__global__ __launch_bounds__(kThreads) void find_kernel(SegState* __restrict__ st,
-                                                        uint32_t* __restrict__ hist) {
-  __shared__ uint32_t wsum[kWaves];
+__global__ __launch_bounds__(kThreads) void find_kernel(SegState* __restrict__ st, int m,
+                                                        const uint32_t* __restrict__ hist) {
+  __shared__ uint32_t fl[kWaves + 8];
   const int j = blockIdx.x;
-  if (st[j].done) return;
-  find_bucket<LEVEL>(st, hist + (size_t)j * kHistBins, j, wsum);
+  SegState s = st[(size_t)LEVEL * m + j];
+  if (!s.done) s = find_bucket<LEVEL>(hist + (size_t)j * kHistStride + hist_offset(LEVEL), s, fl);
+  if (threadIdx.x == 0) st[(size_t)(LEVEL + 1) * m + j] = s;
 }
 
 // Run by one whole workgroup: walks the chunks of segment j
@@ -464,14 +498,14 @@ __global__ __launch_bounds__(kThreads) void find_kernel(SegState* __restrict__ s
 // first selected entry.  Each thread handles kScanPer consecutive chunks per round.
 constexpr int kScanPer = 32;
 __device__ __forceinline__ void scan_segment(const SegDesc* __restrict__ seg,
-                                             const SegState* __restrict__ st, int j,
+                                             const SegState* __restrict__ st, int m, int j,
                                              const uint32_t* __restrict__ chunk_gt,
                                              const uint32_t* __restrict__ chunk_eq,
                                              uint32_t* __restrict__ out_base,
                                              uint32_t* __restrict__ eq_base,
                                              uint32_t* __restrict__ wsum /* 2*kWaves */) {
   const uint32_t c0 = seg[j].chunk_base, c1 = seg[j + 1].chunk_base;
-  const uint32_t r = st[j].r;
+  const uint32_t r = st[(size_t)3 * m + j].r;
   uint32_t carry_eq = 0, carry_out = seg[j].out_off;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   for (uint32_t t0 = c0; t0 < c1; t0 += kThreads * kScanPer) {
@@ -530,18 +564,21 @@ __device__ __forceinline__ void scan_segment(const SegDesc* __restrict__ seg,
 }
 
 // Per chunk: how many keys exceed T and how many equal it.
-template <int ITERS>
+template <int ITERS, bool FUSED>
 __global__ __launch_bounds__(kThreads) void count_kernel(const float* __restrict__ g,
                                                          const SegDesc* __restrict__ seg,
-                                                         const SegState* __restrict__ st, int m,
+                                                         SegState* __restrict__ st, int m,
+                                                         const uint32_t* __restrict__ hist,
                                                          uint32_t* __restrict__ chunk_gt,
                                                          uint32_t* __restrict__ chunk_eq) {
   __shared__ uint32_t red[2 * kWaves];
+  __shared__ uint32_t fl[kWaves + 8];
   const int j = seg_of_chunk(seg, m, blockIdx.x);
   const SegDesc d = seg[j];
-  const uint32_t T = st[j].T;
+  const uint32_t local = blockIdx.x - d.chunk_base;
+  const uint32_t T = state_after<3, FUSED>(st, m, j, hist, local == 0, fl).T;
   Chunk<ITERS> ch;
-  ch.load(g, d.start, (int64_t)d.start + d.size, blockIdx.x - d.chunk_base);
+  ch.load(g, d.start, (int64_t)d.start + d.size, local);
   uint32_t gt = 0, eq = 0;
 #pragma unroll
   for (int i = 0; i < ITERS; ++i) {
@@ -567,13 +604,13 @@ __global__ __launch_bounds__(kThreads) void count_kernel(const float* __restrict
 
 // One workgroup per segment: chunk counts -> output positions.
 __global__ __launch_bounds__(kThreads) void scan_kernel(const SegDesc* __restrict__ seg,
-                                                        const SegState* __restrict__ st,
+                                                        const SegState* __restrict__ st, int m,
                                                         const uint32_t* __restrict__ chunk_gt,
                                                         const uint32_t* __restrict__ chunk_eq,
                                                         uint32_t* __restrict__ out_base,
                                                         uint32_t* __restrict__ eq_base) {
   __shared__ uint32_t wsum[2 * kWaves];
-  scan_segment(seg, st, blockIdx.x, chunk_gt, chunk_eq, out_base, eq_base, wsum);
+  scan_segment(seg, st, m, blockIdx.x, chunk_gt, chunk_eq, out_base, eq_base, wsum);
 }
 
 // Exclusive prefix over the wavefront of a per-lane count in [0, 7], by three ballots.
@@ -586,18 +623,40 @@ __device__ __forceinline__ uint32_t wave_excl_small(uint32_t cnt, uint32_t& tota
          4u * (uint32_t)__popcll(b2 & below);
 }
 
-// Ordered compaction of one chunk.
-template <int ITERS>
+// Ordered compaction of one chunk.  SCAN_HERE: the workgroup sums the counts of the chunks
+// that precede it in its segment itself (ties are granted in index order until the quota r is
+// used up, so the ties taken before this chunk are min(r, equal keys before it)); used when
+// every segment is short enough for that to be cheaper than a separate scan launch.
+template <int ITERS, bool SCAN_HERE>
 __global__ __launch_bounds__(kThreads) void emit_kernel(
     const float* __restrict__ g, const SegDesc* __restrict__ seg, const SegState* __restrict__ st,
-    int m, const uint32_t* __restrict__ chunk_eq, const uint32_t* __restrict__ out_base,
-    const uint32_t* __restrict__ eq_base, int32_t* __restrict__ idx_out,
-    float* __restrict__ val_out) {
+    int m, const uint32_t* __restrict__ chunk_gt, const uint32_t* __restrict__ chunk_eq,
+    const uint32_t* __restrict__ out_base, const uint32_t* __restrict__ eq_base,
+    int32_t* __restrict__ idx_out, float* __restrict__ val_out) {
   __shared__ uint32_t wtot[2][kWaves];
   const int j = seg_of_chunk(seg, m, blockIdx.x);
   const SegDesc d = seg[j];
-  const uint32_t T = st[j].T, r = st[j].r;
-  const uint32_t eb = eq_base[blockIdx.x], ceq = chunk_eq[blockIdx.x];
+  const uint32_t T = st[(size_t)3 * m + j].T, r = st[(size_t)3 * m + j].r;
+  uint32_t eb, ob;
+  if (SCAN_HERE) {
+    uint32_t sg = 0, se = 0;
+    for (uint32_t c = d.chunk_base + threadIdx.x; c < blockIdx.x; c += kThreads) {
+      sg += chunk_gt[c];
+      se += chunk_eq[c];
+    }
+    sg = wave_sum_u32(sg);
+    se = wave_sum_u32(se);
+    if ((threadIdx.x & 63) == 0) { wtot[0][threadIdx.x >> 6] = sg; wtot[1][threadIdx.x >> 6] = se; }
+    __syncthreads();
+    const uint32_t gt_before = wtot[0][0] + wtot[0][1] + wtot[0][2] + wtot[0][3];
+    eb = wtot[1][0] + wtot[1][1] + wtot[1][2] + wtot[1][3];
+    ob = d.out_off + gt_before + min(r, eb);
+    __syncthreads();
+  } else {
+    eb = eq_base[blockIdx.x];
+    ob = out_base[blockIdx.x];
+  }
+  const uint32_t ceq = chunk_eq[blockIdx.x];
   // 0: none of the chunk's ties is taken, 1: all are, 2: the quota ends inside this chunk
   const int mode = (eb >= r) ? 0 : ((r - eb >= ceq) ? 1 : 2);
   Chunk<ITERS> ch;
@@ -658,7 +717,7 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(
   wave_sel = wave_sum_u32(wave_sel);
   if (lane == 0) wtot[0][wave] = wave_sel;
   __syncthreads();
-  uint32_t pos = out_base[blockIdx.x];
+  uint32_t pos = ob;
   for (int w = 0; w < wave; ++w) pos += wtot[0][w];
   if (wtot[0][wave] == 0) return;
   const uint32_t lim = d.out_off + d.k;  // a segment never writes past its own k slots
@@ -708,8 +767,8 @@ SelectLayout select_layout(int64_t m, uint64_t chunks) {
   SelectLayout w;
   size_t o = 0;
   w.seg = o;   o = align_up(o + sizeof(SegDesc) * (size_t)(m + 1), 256);
-  w.st = o;    o = align_up(o + sizeof(SegState) * (size_t)m, 256);
-  w.hist = o;  o = align_up(o + sizeof(uint32_t) * kHistBins * (size_t)m, 256);
+  w.st = o;    o = align_up(o + sizeof(SegState) * 4 * (size_t)m, 256);  // state after 0..3 levels
+  w.hist = o;  o = align_up(o + sizeof(uint32_t) * kHistStride * (size_t)m, 256);
   w.cgt = o;   o = align_up(o + sizeof(uint32_t) * chunks, 256);
   w.ceq = o;   o = align_up(o + sizeof(uint32_t) * chunks, 256);
   w.obase = o; o = align_up(o + sizeof(uint32_t) * chunks, 256);
@@ -736,19 +795,26 @@ inline uint64_t max_chunks(int64_t elems, int64_t m) {
 // histogram workgroup ends by merging up to 2048 bins into the segment's histogram with global
 // atomics, a fixed cost that wants amortising; count/emit have no such tail and balance better
 // with small chunks.
-template <int ITERS, int HITERS>
+template <int ITERS, int HITERS, bool FUSED>
 int launch_select(const float* g, const SegDesc* seg, SegState* st, int m, uint32_t chunks,
                   uint32_t hchunks, uint32_t* hist, uint32_t* cgt, uint32_t* ceq, uint32_t* obase,
-                  uint32_t* ebase, int32_t* idx_out, float* val_out, hipStream_t s) {
-  hist_kernel<HITERS, 0><<<hchunks, kThreads, 0, s>>>(g, seg, st, m, hist);
-  find_kernel<0><<<m, kThreads, 0, s>>>(st, hist);
-  hist_kernel<HITERS, 1><<<hchunks, kThreads, 0, s>>>(g, seg, st, m, hist);
-  find_kernel<1><<<m, kThreads, 0, s>>>(st, hist);
-  hist_kernel<HITERS, 2><<<hchunks, kThreads, 0, s>>>(g, seg, st, m, hist);
-  find_kernel<2><<<m, kThreads, 0, s>>>(st, hist);
-  count_kernel<ITERS><<<chunks, kThreads, 0, s>>>(g, seg, st, m, cgt, ceq);
-  scan_kernel<<<m, kThreads, 0, s>>>(seg, st, cgt, ceq, obase, ebase);
-  emit_kernel<ITERS><<<chunks, kThreads, 0, s>>>(g, seg, st, m, ceq, obase, ebase, idx_out, val_out);
+                  uint32_t* ebase, bool scan_in_emit, int32_t* idx_out, float* val_out,
+                  hipStream_t s) {
+  hist_kernel<HITERS, 0, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, st, m, hist);
+  if (!FUSED) find_kernel<0><<<m, kThreads, 0, s>>>(st, m, hist);
+  hist_kernel<HITERS, 1, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, st, m, hist);
+  if (!FUSED) find_kernel<1><<<m, kThreads, 0, s>>>(st, m, hist);
+  hist_kernel<HITERS, 2, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, st, m, hist);
+  if (!FUSED) find_kernel<2><<<m, kThreads, 0, s>>>(st, m, hist);
+  count_kernel<ITERS, FUSED><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist, cgt, ceq);
+  if (scan_in_emit) {
+    emit_kernel<ITERS, true><<<chunks, kThreads, 0, s>>>(g, seg, st, m, cgt, ceq, obase, ebase,
+                                                         idx_out, val_out);
+  } else {
+    scan_kernel<<<m, kThreads, 0, s>>>(seg, st, m, cgt, ceq, obase, ebase);
+    emit_kernel<ITERS, false><<<chunks, kThreads, 0, s>>>(g, seg, st, m, cgt, ceq, obase, ebase,
+                                                          idx_out, val_out);
+  }
   HIP_TRY(hipGetLastError());
   return DEFT_OK;
 }
@@ -764,12 +830,17 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   const uint32_t hce = (uint32_t)kThreads * 4 * (small ? DEFT_HIST_ITERS_SMALL : DEFT_HIST_ITERS_LARGE);
   std::vector<SegDesc> segs(segs_in);
   uint64_t chunks = 0, hchunks = 0;
+  uint32_t longest = 0;  // chunks of the longest segment
   for (auto& d : segs) {
     d.chunk_base = (uint32_t)chunks;
     d.hchunk_base = (uint32_t)hchunks;
-    chunks += chunks_of(d.start, d.size, ce);
+    const uint32_t c = chunks_of(d.start, d.size, ce);
+    longest = std::max(longest, c);
+    chunks += c;
     hchunks += chunks_of(d.start, d.size, hce);
   }
+  // every emit workgroup can afford to sum its segment's earlier chunk counts itself
+  const bool scan_in_emit = longest <= 2048;
   if (chunks > max_chunks(share, m) || chunks >= (uint64_t(1) << 31)) return DEFT_EWS;
   const SelectLayout w = select_layout(m, chunks);
   if (w.total > ws_bytes) return DEFT_EWS;
@@ -777,7 +848,7 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   SegDesc* seg = reinterpret_cast<SegDesc*>(base + w.seg);
   SegState* st = reinterpret_cast<SegState*>(base + w.st);
   uint32_t* hist = reinterpret_cast<uint32_t*>(base + w.hist);
-  const size_t nzero = (size_t)kHistBins * m;
+  const size_t nzero = (size_t)kHistStride * m;
   const unsigned setup_blocks = (unsigned)std::min<size_t>((nzero + 4 * kThreads - 1) / (4 * kThreads), 256);
   for (int first = 0; first < m; first += kSegBatch) {
     SegBatch b;
@@ -795,10 +866,12 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   uint32_t* ob = reinterpret_cast<uint32_t*>(base + w.obase);
   uint32_t* eb = reinterpret_cast<uint32_t*>(base + w.ebase);
   if (small)
-    return launch_select<DEFT_SEL_ITERS_SMALL, DEFT_HIST_ITERS_SMALL>(
-        g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, idx_out, val_out, s);
-  return launch_select<DEFT_SEL_ITERS_LARGE, DEFT_HIST_ITERS_LARGE>(
-      g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, idx_out, val_out, s);
+    return launch_select<DEFT_SEL_ITERS_SMALL, DEFT_HIST_ITERS_SMALL, true>(
+        g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, scan_in_emit,
+        idx_out, val_out, s);
+  return launch_select<DEFT_SEL_ITERS_LARGE, DEFT_HIST_ITERS_LARGE, false>(
+      g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, scan_in_emit,
+      idx_out, val_out, s);
 }
 
 }  // namespace

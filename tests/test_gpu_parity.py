@@ -200,6 +200,19 @@ def test_select_unaligned_segments_and_subset(deft):
         _check_select(sel, gd, g, off, k, part)
 
 
+def test_select_many_small_segments(deft):
+    """More segments than one descriptor batch holds, sizes 1..600, every start alignment."""
+    rng = np.random.default_rng(21)
+    sizes = [int(x) for x in rng.integers(1, 600, 450)]
+    g = (rng.standard_normal(sum(sizes)) * 10 ** rng.uniform(-3, 1, sum(sizes))).astype(np.float32)
+    sel = _selector(deft, sizes, 1, 0.5, out_cap=sum(sizes))
+    gd = torch.from_numpy(g).to(DEV)
+    off = sel.offsets.tolist()
+    k = [int(rng.integers(0, s + 1)) for s in sizes]
+    _check_select(sel, gd, g, off, k, list(rng.permutation(len(sizes))))
+    _check_select(sel, gd, g, off, k, list(range(0, len(sizes), 3)))
+
+
 def test_deft_single_worker_single_layer_equals_global(deft):
     """Sec. 5.4: with one worker the scheme is the conventional Top-k."""
     _, g = synth.random_layers(5, 1, 300000)
