@@ -57,6 +57,9 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all-ranks", action="store_true", help="also time Alg. 5 on every rank")
+    ap.add_argument("--next-rows", action="store_true",
+                    help="also time the fused error-feedback accumulate + norm pass and the "
+                         "gather/zero step (Alg. 1 around the sparsifier)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one device-to-device copy of the vector (4N read + 4N written), "
                          "the known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE")
@@ -162,6 +165,38 @@ def main():
 
     cm = B.deft_cost_model(sel.sizes, k, owner, n, N, K)
 
+    # ---- the steps of Alg. 1 next to the sparsifier (reported, not part of `value`)
+    next_rows = None
+    if args.next_rows:
+        e_d = torch.zeros_like(g)
+        for _ in range(3):
+            B.deft_accumulate_norms(e_d, g, 0.1, e_d, sel.offsets_dev, sel.sumsq_host, sel.ws)
+        stream.synchronize()
+        a0 = torch.cuda.Event(enable_timing=True); a1 = torch.cuda.Event(enable_timing=True)
+        reps = 10
+        a0.record(stream)
+        for _ in range(reps):
+            B.deft_accumulate_norms(e_d, g, 0.1, e_d, sel.offsets_dev, sel.sumsq_host, sel.ws)
+        a1.record(stream)
+        stream.synchronize()
+        acc_ms = a0.elapsed_time(a1) / reps
+        cnt2 = sel.plan_host(rank, 0)
+        kr2 = sel.enqueue_select(e_d, cnt2, h)
+        stream.synchronize()
+        idx_d = sel.idx_out[:kr2].clone()
+        vals_d = torch.empty(kr2, dtype=torch.float32, device=dev)
+        B.deft_gather_zero(e_d, idx_d, vals_d)
+        stream.synchronize()
+        a0.record(stream)
+        for _ in range(reps):
+            B.deft_gather_zero(e_d, idx_d, vals_d)
+        a1.record(stream)
+        stream.synchronize()
+        next_rows = {"accumulate_norms": {"ms": acc_ms, "GB/s": 12.0 * N / (acc_ms * 1e-3) / 1e9,
+                                          "bytes": "8N read + 4N written"},
+                     "gather_zero": {"ms": a0.elapsed_time(a1) / reps, "count": kr2}}
+        del e_d
+
     # ---- roofline of the dominant kernel (norm pass: reads every element once)
     norm_avg_ms = sum(norm_ms) / len(norm_ms)
     achieved = 4.0 * N / (norm_avg_ms * 1e-3) / 1e9
@@ -204,6 +239,8 @@ def main():
     }
     if per_rank is not None:
         out["per_rank_select"] = per_rank
+    if next_rows is not None:
+        out["next_rows"] = next_rows
     if not args.no_cpu_baseline:
         cb, o_idx = cpu_baseline(gs, sel.offsets.tolist(), rank)
         out["cpu_baseline"] = cb

@@ -168,6 +168,34 @@ int topk_global(const float* g_dev, int64_t N, int64_t K, int32_t* idx_out_dev,
                 float* val_out_dev, void* ws_dev, size_t ws_bytes, void* stream);
 
 /*
+ * Alg. 1, the step before the sparsifier, fused with the norm pass of Sec. 4.2:
+ *   acc[i] = e[i] + eta * grad[i]   (fp32: product rounded, then sum rounded; no fused
+ *                                    multiply-add)
+ *   sumsq[l] = sum over layer l of acc[i]^2   (fp64, as deft_layer_norms)
+ * in one pass (8 bytes read, 4 written per element instead of two passes).
+ *   e_dev, grad_dev  in   N floats each, device, 16-byte aligned
+ *   acc_dev          out  N floats, device, 16-byte aligned; may be the same buffer as e_dev
+ *                         (in-place error feedback); must not overlap grad_dev otherwise
+ *   offsets_dev, sumsq_dev, ws_dev, ws_bytes: as for deft_layer_norms (DEFT_OP_NORMS)
+ * Errors: DEFT_EINVAL, DEFT_ERANGE, DEFT_EWS, DEFT_EHIP.
+ */
+int deft_accumulate_norms(const float* e_dev, const float* grad_dev, float eta, float* acc_dev,
+                          int64_t N, const int64_t* offsets_dev, int32_t L, double* sumsq_dev,
+                          void* ws_dev, size_t ws_bytes, void* stream);
+
+/*
+ * Alg. 1, the steps after the index exchange: vals[i] = acc[idx[i]], then acc[idx[i]] = +0, so
+ * that acc becomes the next local error.  idx holds `count` distinct positions in [0, N)
+ * (the selected indices of all workers are distinct because their layers are disjoint,
+ * Sec. 4.3); entries outside [0, N) are skipped and their vals[i] set to 0.  Duplicate
+ * entries give unspecified vals for the duplicates.
+ *   acc_dev  in/out N floats, device;  idx_dev in, count int32, device;  vals_out_dev out
+ * Errors: DEFT_EINVAL (null with count > 0, count < 0, N < 1), DEFT_ERANGE, DEFT_EHIP.
+ */
+int deft_gather_zero(float* acc_dev, int64_t N, const int32_t* idx_dev, int64_t count,
+                     float* vals_out_dev, void* stream);
+
+/*
  * Upper bound on the scratch bytes of a device call.
  *   DEFT_OP_NORMS:        elems = N,            count = L
  *   DEFT_OP_SELECT:       elems = total size of the selected layers (N always suffices),

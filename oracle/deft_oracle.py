@@ -37,6 +37,7 @@ import numpy as np
 __all__ = [
     "partition", "layer_sumsq", "layer_norms", "total_k", "alloc_k", "layer_costs",
     "assign_layers", "magnitude_key", "topk_segment", "select", "topk_global", "cost_model",
+    "accumulate", "gather_zero",
 ]
 
 
@@ -251,3 +252,26 @@ def cost_model(sizes: Sequence[int], k: Sequence[int], alloc_bin: Sequence[Seque
         "C_trivial": C_triv,
         "f_trivial": topk_cost / C_triv if C_triv > 0 else math.inf,
     }
+
+
+# --------------------------------------------------------------------------------------
+# Alg. 1 -- the steps around the sparsifier (error feedback)
+# --------------------------------------------------------------------------------------
+def accumulate(e: np.ndarray, grad: np.ndarray, eta: float) -> np.ndarray:
+    """acc = e + eta * G  (Alg. 1, the step before Sparsify), in fp32 like the vectors
+    themselves: the product is rounded to fp32, then the sum is rounded to fp32 (two separate
+    operations, no fused multiply-add)."""
+    e = np.ascontiguousarray(e, dtype=np.float32)
+    grad = np.ascontiguousarray(grad, dtype=np.float32)
+    prod = np.multiply(grad, np.float32(eta), dtype=np.float32)
+    return np.add(e, prod, dtype=np.float32)
+
+
+def gather_zero(acc: np.ndarray, idx: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """g_i = acc[idx]; acc[idx] = 0; e_next = acc  (Alg. 1, the steps after the index
+    exchange).  idx holds distinct positions.  Returns (values, e_next); acc is not modified."""
+    idx = np.asarray(idx, dtype=np.int64)
+    vals = acc[idx].copy()
+    e_next = acc.copy()
+    e_next[idx] = np.float32(0.0)
+    return vals, e_next

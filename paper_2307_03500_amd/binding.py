@@ -27,6 +27,9 @@ SIGNATURES = {
     "deft_check_layout": (C.c_int, [_P, C.c_int32, C.c_int64]),
     "deft_layer_norms": (C.c_int, [_P, C.c_int64, _P, C.c_int32, _P, _P, C.c_size_t, _P]),
     "deft_norms_from_sumsq": (C.c_int, [_P, C.c_int32, _P]),
+    "deft_accumulate_norms": (C.c_int, [_P, _P, C.c_float, _P, C.c_int64, _P, C.c_int32, _P, _P,
+                                        C.c_size_t, _P]),
+    "deft_gather_zero": (C.c_int, [_P, C.c_int64, _P, C.c_int64, _P, _P]),
     "deft_alloc_k": (C.c_int, [_P, _P, C.c_int32, C.c_int64, C.c_double, _P]),
     "deft_assign_layers": (C.c_int, [_P, _P, C.c_int32, C.c_int32, C.c_int64, C.c_int32, _P, _P, _P]),
     "deft_cost_model": (C.c_int, [_P, _P, _P, C.c_int32, C.c_int32, C.c_int64, C.c_int64, _P, _P]),
@@ -155,6 +158,21 @@ def deft_layer_norms(g, offsets_dev, sumsq, ws, stream=None) -> None:
                                   sumsq.data_ptr(), ws.data_ptr(),
                                   ws.numel() * ws.element_size(), _stream(stream)),
            "deft_layer_norms")
+
+
+def deft_accumulate_norms(e, grad, eta: float, acc, offsets_dev, sumsq, ws, stream=None) -> None:
+    """acc = e + eta*grad (fp32) and the per-layer sums of squares of acc, one pass.  acc may be e."""
+    L = offsets_dev.numel() - 1
+    _check(lib().deft_accumulate_norms(e.data_ptr(), grad.data_ptr(), float(eta), acc.data_ptr(),
+                                       e.numel(), offsets_dev.data_ptr(), L, sumsq.data_ptr(),
+                                       ws.data_ptr(), ws.numel() * ws.element_size(),
+                                       _stream(stream)), "deft_accumulate_norms")
+
+
+def deft_gather_zero(acc, idx, vals_out, stream=None) -> None:
+    """vals_out[i] = acc[idx[i]]; acc[idx[i]] = 0.  idx: int32 cuda tensor of distinct positions."""
+    _check(lib().deft_gather_zero(acc.data_ptr(), acc.numel(), idx.data_ptr(), idx.numel(),
+                                  vals_out.data_ptr(), _stream(stream)), "deft_gather_zero")
 
 
 def deft_select(g, offsets_host, k_host, my_layers_host, idx_out, val_out, ws, stream=None) -> np.ndarray:

@@ -74,14 +74,27 @@ __device__ __forceinline__ int layer_of(const int64_t* __restrict__ off, int L, 
 // every 16-byte load is aligned.  A chunk that lies inside one layer writes one partial
 // (head).  A chunk holding layer boundaries writes the part of the layer it starts in (head),
 // the part of the layer it ends in (tail) and finishes the layers that lie wholly inside it.
-#ifndef DEFT_NORM_MODE
-#define DEFT_NORM_MODE 0
-#endif
-#ifndef DEFT_NORM_GRID
-#define DEFT_NORM_GRID 0
-#endif
+// Source of the values that are normed.  Plain: the vector itself.  Accumulating (Alg. 1, the
+// step before the sparsifier): acc = e + eta * grad in fp32 -- product rounded, then sum
+// rounded -- written back to `acc` on the way.
+struct NormSrc {
+  const float* g;                // plain: the vector; accumulating: the local error e
+  const float* __restrict__ gr;  // accumulating: the fresh gradient
+  float* acc;                    // accumulating: output (may alias g)
+  float eta;
+};
+
+template <bool ACC>
+__device__ __forceinline__ float norm_value(const NormSrc& src, int64_t i) {
+  if (!ACC) return src.g[i];
+  const float v = __fadd_rn(src.g[i], __fmul_rn(src.eta, src.gr[i]));
+  src.acc[i] = v;
+  return v;
+}
+
+template <bool ACC>
 __device__ __forceinline__ void norm_one_chunk(
-    const float* __restrict__ g, int64_t N, const int64_t* __restrict__ off, int L,
+    const NormSrc& src, int64_t N, const int64_t* __restrict__ off, int L,
     double* __restrict__ head, double* __restrict__ tail, double* __restrict__ sumsq,
     int64_t chunk, double* red) {
   const int64_t cs = chunk * kNormChunk;
@@ -90,21 +103,25 @@ __device__ __forceinline__ void norm_one_chunk(
   if (off[lf + 1] >= ce) {
     double a0 = 0.0, a1 = 0.0;
     if (ce - cs == kNormChunk) {
-      const float4* __restrict__ p = reinterpret_cast<const float4*>(g + cs);
+      const float4* __restrict__ p = reinterpret_cast<const float4*>(src.g + cs);
       float4 v[kNormIters];
 #pragma unroll
-#if DEFT_NORM_MODE == 2
-      for (int i = 0; i < kNormIters; ++i) v[i] = __builtin_nontemporal_load(&p[threadIdx.x + i * kThreads]);
-#else
       for (int i = 0; i < kNormIters; ++i) v[i] = p[threadIdx.x + i * kThreads];
-#endif
-#if DEFT_NORM_MODE == 1
-      float f = 0.f;
+      if (ACC) {
+        const float4* __restrict__ q = reinterpret_cast<const float4*>(src.gr + cs);
+        float4 w[kNormIters];
 #pragma unroll
-      for (int i = 0; i < kNormIters; ++i) f += v[i].x + v[i].y + v[i].z + v[i].w;
-      if (f == 1.2345f) head[chunk] = f;
-      return;
-#endif
+        for (int i = 0; i < kNormIters; ++i) w[i] = q[threadIdx.x + i * kThreads];
+        float4* o = reinterpret_cast<float4*>(src.acc + cs);
+#pragma unroll
+        for (int i = 0; i < kNormIters; ++i) {
+          v[i].x = __fadd_rn(v[i].x, __fmul_rn(src.eta, w[i].x));
+          v[i].y = __fadd_rn(v[i].y, __fmul_rn(src.eta, w[i].y));
+          v[i].z = __fadd_rn(v[i].z, __fmul_rn(src.eta, w[i].z));
+          v[i].w = __fadd_rn(v[i].w, __fmul_rn(src.eta, w[i].w));
+          o[threadIdx.x + i * kThreads] = v[i];
+        }
+      }
 #pragma unroll
       for (int i = 0; i < kNormIters; ++i) {
         const double x = v[i].x, y = v[i].y, z = v[i].z, w = v[i].w;
@@ -115,7 +132,7 @@ __device__ __forceinline__ void norm_one_chunk(
       }
     } else {
       for (int64_t i = cs + threadIdx.x; i < ce; i += kThreads) {
-        const double x = g[i];
+        const double x = norm_value<ACC>(src, i);
         a0 = fma(x, x, a0);
       }
     }
@@ -130,7 +147,7 @@ __device__ __forceinline__ void norm_one_chunk(
     const int64_t s = max(cs, lo), e = min(ce, hi);
     double a = 0.0;
     for (int64_t i = s + threadIdx.x; i < e; i += kThreads) {
-      const double x = g[i];
+      const double x = norm_value<ACC>(src, i);
       a = fma(x, x, a);
     }
     const double t = block_sum(a, red);
@@ -143,13 +160,25 @@ __device__ __forceinline__ void norm_one_chunk(
   }
 }
 
+template <bool ACC>
 __global__ __launch_bounds__(kThreads) void norm_chunks_kernel(
-    const float* __restrict__ g, int64_t N, const int64_t* __restrict__ off, int L,
-    double* __restrict__ head, double* __restrict__ tail, double* __restrict__ sumsq,
-    int64_t n_chunks) {
+    NormSrc src, int64_t N, const int64_t* __restrict__ off, int L, double* __restrict__ head,
+    double* __restrict__ tail, double* __restrict__ sumsq) {
   __shared__ double red[kWaves];
-  for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x)
-    norm_one_chunk(g, N, off, L, head, tail, sumsq, c, red);
+  norm_one_chunk<ACC>(src, N, off, L, head, tail, sumsq, blockIdx.x, red);
+}
+
+// vals[i] = acc[idx[i]]; acc[idx[i]] = 0   (Alg. 1, the steps after the index exchange)
+__global__ __launch_bounds__(kThreads) void gather_zero_kernel(float* __restrict__ acc, int64_t N,
+                                                               const int32_t* __restrict__ idx,
+                                                               int64_t count,
+                                                               float* __restrict__ vals) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= count) return;
+  const int64_t j = idx[i];
+  if (j < 0 || j >= N) { vals[i] = 0.0f; return; }
+  vals[i] = acc[j];
+  acc[j] = 0.0f;
 }
 
 // One workgroup per layer adds the partials of the chunks the layer touches, in chunk order
@@ -895,21 +924,58 @@ extern "C" size_t deft_workspace_bytes(int op, int64_t elems, int32_t count) {
   }
 }
 
-extern "C" int deft_layer_norms(const float* g_dev, int64_t N, const int64_t* offsets_dev,
-                                int32_t L, double* sumsq_dev, void* ws_dev, size_t ws_bytes,
-                                void* stream) {
-  if (!g_dev || !offsets_dev || !sumsq_dev || !ws_dev || L < 1 || N < 1) return DEFT_EINVAL;
+namespace {
+int run_norms(const float* g, const float* grad, float eta, float* acc, int64_t N,
+              const int64_t* offsets_dev, int32_t L, double* sumsq_dev, void* ws_dev,
+              size_t ws_bytes, void* stream) {
+  if (!g || !offsets_dev || !sumsq_dev || !ws_dev || L < 1 || N < 1) return DEFT_EINVAL;
   if (N > kMaxN) return DEFT_ERANGE;
-  if ((reinterpret_cast<uintptr_t>(g_dev) & 15u) || (reinterpret_cast<uintptr_t>(ws_dev) & 15u))
+  if ((reinterpret_cast<uintptr_t>(g) & 15u) || (reinterpret_cast<uintptr_t>(ws_dev) & 15u))
     return DEFT_EINVAL;
   if (ws_bytes < deft_workspace_bytes(DEFT_OP_NORMS, N, L)) return DEFT_EWS;
   const unsigned chunks = (unsigned)((N + kNormChunk - 1) / kNormChunk);
   double* head = static_cast<double*>(ws_dev);
   double* tail = head + chunks;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const unsigned grid = DEFT_NORM_GRID > 0 ? std::min<unsigned>(chunks, DEFT_NORM_GRID) : chunks;
-  norm_chunks_kernel<<<grid, kThreads, 0, s>>>(g_dev, N, offsets_dev, L, head, tail, sumsq_dev, chunks);
+  NormSrc src;
+  src.g = g; src.gr = grad; src.acc = acc; src.eta = eta;
+  if (acc)
+    norm_chunks_kernel<true><<<chunks, kThreads, 0, s>>>(src, N, offsets_dev, L, head, tail, sumsq_dev);
+  else
+    norm_chunks_kernel<false><<<chunks, kThreads, 0, s>>>(src, N, offsets_dev, L, head, tail, sumsq_dev);
   norm_finish_kernel<<<L, kThreads, 0, s>>>(offsets_dev, N, head, tail, sumsq_dev);
+  HIP_TRY(hipGetLastError());
+  return DEFT_OK;
+}
+}  // namespace
+
+extern "C" int deft_layer_norms(const float* g_dev, int64_t N, const int64_t* offsets_dev,
+                                int32_t L, double* sumsq_dev, void* ws_dev, size_t ws_bytes,
+                                void* stream) {
+  return run_norms(g_dev, nullptr, 0.0f, nullptr, N, offsets_dev, L, sumsq_dev, ws_dev, ws_bytes,
+                   stream);
+}
+
+extern "C" int deft_accumulate_norms(const float* e_dev, const float* grad_dev, float eta,
+                                     float* acc_dev, int64_t N, const int64_t* offsets_dev,
+                                     int32_t L, double* sumsq_dev, void* ws_dev, size_t ws_bytes,
+                                     void* stream) {
+  if (!grad_dev || !acc_dev) return DEFT_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(grad_dev) & 15u) || (reinterpret_cast<uintptr_t>(acc_dev) & 15u))
+    return DEFT_EINVAL;
+  return run_norms(e_dev, grad_dev, eta, acc_dev, N, offsets_dev, L, sumsq_dev, ws_dev, ws_bytes,
+                   stream);
+}
+
+extern "C" int deft_gather_zero(float* acc_dev, int64_t N, const int32_t* idx_dev, int64_t count,
+                                float* vals_out_dev, void* stream) {
+  if (count < 0 || N < 1) return DEFT_EINVAL;
+  if (N > kMaxN || count > kMaxN) return DEFT_ERANGE;
+  if (count == 0) return DEFT_OK;
+  if (!acc_dev || !idx_dev || !vals_out_dev) return DEFT_EINVAL;
+  const unsigned blocks = (unsigned)((count + kThreads - 1) / kThreads);
+  gather_zero_kernel<<<blocks, kThreads, 0, static_cast<hipStream_t>(stream)>>>(
+      acc_dev, N, idx_dev, count, vals_out_dev);
   HIP_TRY(hipGetLastError());
   return DEFT_OK;
 }

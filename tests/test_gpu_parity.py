@@ -236,6 +236,86 @@ def test_select_repeatable_and_workspace_reuse(deft):
     assert ai.tolist() == b.idx.tolist() and (_bits(av) == _bits(b.val)).all()
 
 
+# ------------------------------------------------------------------------------ Alg. 1 neighbours
+@pytest.mark.parametrize("name", ["toy_mlp", "resnet18", "lstm_lm"])
+@pytest.mark.parametrize("in_place", [False, True])
+def test_accumulate_norms_configs(deft, name, in_place):
+    gs = synth.make(name, seed=3)
+    rng = np.random.default_rng(5)
+    e = (rng.standard_normal(gs.N) * 1e-3).astype(np.float32)
+    eta = 0.1
+    sel = _selector(deft, gs.tensor_sizes, gs.n_workers, gs.d)
+    e_d = torch.from_numpy(e).to(DEV)
+    g_d = torch.from_numpy(gs.g).to(DEV)
+    acc_d = e_d if in_place else torch.empty_like(e_d)
+    deft.deft_accumulate_norms(e_d, g_d, eta, acc_d, sel.offsets_dev, sel.sumsq_host, sel.ws)
+    torch.cuda.synchronize()
+    want = O.accumulate(e, gs.g, eta)
+    assert (_bits(acc_d.cpu().numpy()) == _bits(want)).all()
+    got = deft.deft_norms_from_sumsq(sel.sumsq_host.numpy())
+    _check_norms(got, O.layer_norms(want, sel.offsets.tolist()))
+
+
+def test_accumulate_norms_ragged(deft):
+    sizes = [1, 63, 64, 65, 4095, 4097, 1, 1, 16384, 3, 8190, 4, 8190, 5]
+    N = sum(sizes)
+    rng = np.random.default_rng(6)
+    e = rng.standard_normal(N).astype(np.float32)
+    g = (rng.standard_normal(N) * 10 ** rng.uniform(-3, 3, N)).astype(np.float32)
+    sel = _selector(deft, sizes, 1, 0.5)
+    e_d, g_d = torch.from_numpy(e).to(DEV), torch.from_numpy(g).to(DEV)
+    deft.deft_accumulate_norms(e_d, g_d, -0.37, e_d, sel.offsets_dev, sel.sumsq_host, sel.ws)
+    torch.cuda.synchronize()
+    want = O.accumulate(e, g, -0.37)
+    assert (_bits(e_d.cpu().numpy()) == _bits(want)).all()
+    _check_norms(deft.deft_norms_from_sumsq(sel.sumsq_host.numpy()), O.layer_norms(want, sel.offsets.tolist()))
+
+
+def test_one_error_feedback_iteration_all_workers(deft):
+    """Alg. 1 around the sparsifier on one vector playing every worker: accumulate -> DEFT on
+    each rank -> concatenate the indices (the all-gather) -> gather the values and zero them."""
+    gs = synth.make("resnet18", seed=2)
+    e = np.zeros(gs.N, np.float32)
+    eta = 0.05
+    sel = _selector(deft, gs.tensor_sizes, gs.n_workers, gs.d)
+    acc_d = torch.from_numpy(e).to(DEV)
+    g_d = torch.from_numpy(gs.g).to(DEV)
+    deft.deft_accumulate_norms(acc_d, g_d, eta, acc_d, sel.offsets_dev, sel.sumsq_host, sel.ws)
+    torch.cuda.synchronize()
+    norms = deft.deft_norms_from_sumsq(sel.sumsq_host.numpy())
+    parts = []
+    for r in range(gs.n_workers):
+        res = sel.select(acc_d, rank=r)
+        assert res.norms.tolist() == norms.tolist()  # same bits from either norm entry point
+        parts.append(res.idx_dev.clone())
+    idx_d = torch.cat(parts)
+    vals_d = torch.empty(idx_d.numel(), dtype=torch.float32, device=DEV)
+    deft.deft_gather_zero(acc_d, idx_d, vals_d)
+    torch.cuda.synchronize()
+    # oracle
+    o_acc = O.accumulate(e, gs.g, eta)
+    off, lay = sel.offsets.tolist(), sel.sizes.tolist()
+    o_k = O.alloc_k(O.layer_norms(o_acc, off), lay, gs.N, gs.d)
+    o_idx = np.concatenate([O.select(o_acc, off, o_k, O.assign_layers(lay, o_k, gs.n_workers, 0, r)[1])[0]
+                            for r in range(gs.n_workers)])
+    o_vals, o_next = O.gather_zero(o_acc, o_idx)
+    assert idx_d.cpu().numpy().tolist() == o_idx.tolist()
+    assert (_bits(vals_d.cpu().numpy()) == _bits(o_vals)).all()
+    assert (_bits(acc_d.cpu().numpy()) == _bits(o_next)).all()
+    assert len(np.unique(o_idx)) == len(o_idx) == sum(o_k)  # density kept, no build-up (Sec. 4.3)
+
+
+def test_gather_zero_edge_cases(deft):
+    acc = torch.arange(1, 11, dtype=torch.float32, device=DEV)
+    idx = torch.tensor([9, 0, 4, -1, 10], dtype=torch.int32, device=DEV)  # two out of range
+    vals = torch.full((5,), 99.0, dtype=torch.float32, device=DEV)
+    deft.deft_gather_zero(acc, idx, vals)
+    deft.deft_gather_zero(acc, idx[:0], vals[:0])  # empty list: nothing enqueued
+    torch.cuda.synchronize()
+    assert vals.cpu().tolist() == [10.0, 1.0, 5.0, 0.0, 0.0]
+    assert acc.cpu().tolist() == [0.0, 2.0, 3.0, 4.0, 0.0, 6.0, 7.0, 8.0, 9.0, 0.0]
+
+
 # ------------------------------------------------------------------------------ full size
 def _verify_topk_by_threshold(g, idx, val, s, e, k):
     """O(n) check that idx is exactly the Top-k of g[s:e] under the tie rule: there is a key T

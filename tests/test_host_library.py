@@ -188,6 +188,27 @@ def test_device_calls_reject_bad_arguments_before_touching_the_gpu(deft):
     assert norms(wsb=8) == B.DEFT_EWS
     assert norms(g=0x1008) == B.DEFT_EINVAL
 
+    def accn(e=0x1000, gr=0x7000, acc=0x1000, N=16, offd=0x5000, L=2, out=0x6000, ws=0x4000, wsb=1 << 20):
+        return lib.deft_accumulate_norms(C.c_void_p(e), C.c_void_p(gr), 0.1, C.c_void_p(acc), N,
+                                         C.c_void_p(offd), L, C.c_void_p(out), C.c_void_p(ws), wsb, None)
+
+    assert accn(gr=0) == B.DEFT_EINVAL
+    assert accn(acc=0) == B.DEFT_EINVAL
+    assert accn(acc=0x1004) == B.DEFT_EINVAL
+    assert accn(e=0) == B.DEFT_EINVAL
+    assert accn(N=2 ** 31) == B.DEFT_ERANGE
+    assert accn(wsb=8) == B.DEFT_EWS
+
+    def gz(acc=0x1000, N=16, idx=0x2000, count=4, vals=0x3000):
+        return lib.deft_gather_zero(C.c_void_p(acc), N, C.c_void_p(idx), count, C.c_void_p(vals), None)
+
+    assert gz(count=-1) == B.DEFT_EINVAL
+    assert gz(acc=0) == B.DEFT_EINVAL
+    assert gz(idx=0) == B.DEFT_EINVAL
+    assert gz(N=0) == B.DEFT_EINVAL
+    assert gz(N=2 ** 31) == B.DEFT_ERANGE
+    assert gz(count=0, acc=0, idx=0, vals=0) == B.DEFT_OK
+
     def topk(g=0x1000, N=16, K=4, idx=0x2000, val=0x3000, ws=0x4000, wsb=1 << 20):
         return lib.topk_global(C.c_void_p(g), N, K, C.c_void_p(idx), C.c_void_p(val),
                                C.c_void_p(ws), wsb, None)

@@ -339,3 +339,39 @@ def test_deft_with_one_worker_one_layer_is_global_topk():
     idx, val, _ = O.select(g, off, k, part)
     gi, gv = O.topk_global(g, O.total_k(len(g), 0.02))
     assert idx.tolist() == gi.tolist() and val.tolist() == gv.tolist()
+
+
+# ------------------------------------------------------------------ Alg. 1 neighbours
+def test_accumulate_hand_values_and_double_reference():
+    # exactly representable cases
+    e = np.array([1.0, -2.0, 0.0, 0.5], np.float32)
+    g = np.array([2.0, 4.0, -8.0, 0.0], np.float32)
+    assert O.accumulate(e, g, 0.5).tolist() == [2.0, 0.0, -4.0, 0.5]
+    # rounding: 0.1f * 3 is rounded to fp32 before the add (a fused multiply-add would differ)
+    rng = np.random.default_rng(9)
+    e = rng.standard_normal(20000).astype(np.float32)
+    g = rng.standard_normal(20000).astype(np.float32)
+    eta = np.float32(0.1)
+    # fp64 holds the product of two fp32 exactly; its fp32 rounding is the correctly rounded
+    # product.  With |exponent gap| small the fp64 sum is exact as well, so one more rounding
+    # gives the correctly rounded fp32 sum: an independent route to the same two-step result.
+    prod = (np.float64(eta) * g.astype(np.float64)).astype(np.float32)
+    want = (e.astype(np.float64) + prod.astype(np.float64)).astype(np.float32)
+    got = O.accumulate(e, g, float(eta))
+    assert (got.view(np.uint32) == want.view(np.uint32)).all()
+    fused = (e.astype(np.float64) + np.float64(eta) * g.astype(np.float64)).astype(np.float32)
+    assert (fused.view(np.uint32) != want.view(np.uint32)).any()  # the distinction is real
+
+
+def test_gather_zero_hand_example_and_invariants():
+    acc = np.array([0.5, -1.5, 2.0, 0.0, -3.0, 7.0], np.float32)
+    vals, e_next = O.gather_zero(acc, [1, 4, 5])
+    assert vals.tolist() == [-1.5, -3.0, 7.0]
+    assert e_next.tolist() == [0.5, 0.0, 2.0, 0.0, 0.0, 0.0]
+    assert acc.tolist() == [0.5, -1.5, 2.0, 0.0, -3.0, 7.0]  # input untouched
+    # what is sent plus what is kept is the accumulator (Alg. 1: nothing is lost)
+    back = e_next.copy()
+    back[[1, 4, 5]] += vals
+    assert back.tolist() == acc.tolist()
+    v0, e0 = O.gather_zero(acc, [])
+    assert len(v0) == 0 and e0.tolist() == acc.tolist()
