@@ -47,6 +47,58 @@ def cpu_baseline(gs, offsets, rank):
             "seconds": t1 - t0}, idx
 
 
+def sweep_workers(args, ns):
+    """Fig. 9 analogue: time of the layer-wise selection of the slowest worker (Eq. 5) against
+    the conventional Top-k over the whole vector, as the number of workers grows.  Every rank's
+    real share is timed on the one GPU, one after the other."""
+    import numpy as np
+    import torch
+    from paper_2307_03500_amd import binding as B
+    from paper_2307_03500_amd import pipeline, synth
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    gs = synth.make(args.config, seed=args.seed)
+    g = torch.from_numpy(gs.g).to(dev)
+    stream = torch.cuda.current_stream()
+    h = stream.cuda_stream
+
+    def timeit(fn, warm=3, reps=10):
+        for _ in range(warm):
+            fn()
+        stream.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+            stream.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / reps
+
+    rows = []
+    global_ms = None
+    for n in ns:
+        sel = pipeline.DeftSelector(gs.tensor_sizes, n, gs.d, dev)
+        if global_ms is None:
+            global_ms = timeit(lambda: B.topk_global(g, sel.K, sel.idx_out, sel.val_out, sel.ws))
+        norm_ms = timeit(lambda: sel.enqueue_norms(g, h))
+        sel.enqueue_norms(g, h)
+        stream.synchronize()
+        per = []
+        for r in range(n):
+            cnt = sel.plan_host(r, 0)
+            per.append(timeit(lambda: sel.enqueue_select(g, cnt, h), warm=2, reps=5))
+        owner = sel.owner_h.copy()
+        cm = B.deft_cost_model(sel.sizes, sel.k_h, owner, n, gs.N, sel.K)
+        rows.append({"n": n, "layers": sel.L, "select_ms_max": max(per),
+                     "select_ms_mean": sum(per) / len(per), "norm_ms": norm_ms,
+                     "speedup_select": global_ms / max(per),
+                     "speedup_whole": global_ms / (norm_ms + max(per)),
+                     "f_n": cm["f_n"], "f_trivial": cm["f_trivial"]})
+        del sel
+    print(json.dumps({"metric": "selection speedup over conventional Top-k vs number of workers",
+                      "config": {"workload": f"{args.config}-shaped gradient set, seed {args.seed}, "
+                                             f"d={gs.d}", "N": gs.N},
+                      "topk_global_ms": global_ms, "sweep": rows, "data": "synthetic"}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -63,6 +115,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one device-to-device copy of the vector (4N read + 4N written), "
                          "the known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--sweep-workers", default="",
+                    help="comma-separated worker counts: print the selection-speedup curve "
+                         "(the analogue of the paper's Fig. 9) instead of the benchmark line")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU (one worker's share of an n-worker job); "
@@ -77,6 +132,9 @@ def main():
         import __graft_entry__
         __graft_entry__.build()
     B.lib()
+    if args.sweep_workers:
+        sweep_workers(args, [int(x) for x in args.sweep_workers.split(",")])
+        return
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 

@@ -451,24 +451,153 @@ __device__ __forceinline__ SegState state_after(SegState* __restrict__ st, int m
   return s;
 }
 
-// Digit histogram of one level.  Level 0 counts every element; deeper levels count only the
-// elements whose higher bits equal the prefix chosen so far.
-template <int ITERS, int LEVEL, bool FUSED>
-__global__ __launch_bounds__(kThreads) void hist_kernel(const float* __restrict__ g,
-                                                        const SegDesc* __restrict__ seg,
-                                                        SegState* __restrict__ st, int m,
-                                                        uint32_t* __restrict__ hist) {
-  constexpr int kBits = LEVEL == 0 ? kBits0 : (LEVEL == 1 ? kBits1 : kBits2);
-  constexpr int kShift = LEVEL == 0 ? (kBits1 + kBits2) : (LEVEL == 1 ? kBits2 : 0);
-  constexpr int kBins = 1 << kBits;
+// Pass 1 of 3 over the segment: histogram of the top digit (11 bits) of every key.
+template <int HITERS, bool FUSED>
+__global__ __launch_bounds__(kThreads) void hist0_kernel(const float* __restrict__ g,
+                                                         const SegDesc* __restrict__ seg, int m,
+                                                         uint32_t* __restrict__ hist) {
+  constexpr int kBins = 1 << kBits0;
+  constexpr int kShift = kBits1 + kBits2;
+  __shared__ uint32_t lh[kBins];
+  const int j = seg_of_hchunk(seg, m, blockIdx.x);
+  const SegDesc d = seg[j];
+  for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
+  __syncthreads();
+  Chunk<HITERS> ch;
+  ch.load(g, d.start, (int64_t)d.start + d.size, blockIdx.x - d.hchunk_base);
+#pragma unroll
+  for (int i = 0; i < HITERS; ++i) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const bool on = (ch.valid[i] >> c) & 1u;
+      const uint32_t digit = ch.key[i][c] >> kShift;
+      // Gradients cluster in few exponent buckets: let the lanes that share the first active
+      // lane's digit add once, the rest add individually.
+      const unsigned long long act = __ballot(on);
+      if (act) {
+        const int leader = __ffsll((long long)act) - 1;
+        const uint32_t dl = (uint32_t)__builtin_amdgcn_readlane((int)digit, leader);
+        const unsigned long long same = __ballot(on && digit == dl);
+        if (on) {
+          if (digit == dl) {
+            if ((int)(threadIdx.x & 63) == leader) atomicAdd(&lh[dl], (uint32_t)__popcll(same));
+          } else {
+            atomicAdd(&lh[digit], 1u);
+          }
+        }
+      }
+    }
+  }
+  __syncthreads();
+  uint32_t* gh = hist + (size_t)j * kHistStride + hist_offset(0);
+  for (int b = threadIdx.x; b < kBins; b += kThreads) {
+    const uint32_t v = lh[b];
+    if (v) atomicAdd(&gh[b], v);
+  }
+}
+
+// Pass 2 of 3 over the segment.  The top digit b0 of the threshold is known.  Keys with a
+// larger top digit are selected for sure and are only counted, per count/emit chunk; keys with
+// top digit b0 ("candidates", about as many as k) are histogrammed on their next digit AND
+// their low 20 bits are parked in a small per-chunk slot array, so that the remaining digit
+// levels and the per-chunk counts can be worked out from the slots without reading the
+// segment again.  A chunk with more candidates than slots is marked by its count; the later
+// kernels read such a chunk from the segment instead (heavy ties, dense selections).
+// A workgroup handles one histogram chunk = 4 count/emit chunks, one per wavefront.
+template <int ITERS, bool FUSED>
+__global__ __launch_bounds__(kThreads) void pass2_kernel(
+    const float* __restrict__ g, const SegDesc* __restrict__ seg, SegState* __restrict__ st, int m,
+    uint32_t* __restrict__ hist, uint32_t* __restrict__ n_sure, uint32_t* __restrict__ cand_cnt,
+    uint32_t* __restrict__ slots, uint32_t cap) {
+  constexpr int HITERS = 4 * ITERS;
+  constexpr int kBins = 1 << kBits1;
   __shared__ uint32_t lh[kBins];
   __shared__ uint32_t fl[kWaves + 8];
   const int j = seg_of_hchunk(seg, m, blockIdx.x);
   const SegDesc d = seg[j];
   const uint32_t local = blockIdx.x - d.hchunk_base;
-  const SegState s = state_after<LEVEL, FUSED>(st, m, j, hist, local == 0, fl);
+  const SegState s = state_after<1, FUSED>(st, m, j, hist, local == 0, fl);
+  const uint32_t b0 = s.done ? (s.T >> (kBits1 + kBits2)) : s.prefix;
+  for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
+  __syncthreads();
+  Chunk<HITERS> ch;
+  ch.load(g, d.start, (int64_t)d.start + d.size, local);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t n_chunks = seg[j + 1].chunk_base - d.chunk_base;
+  const uint32_t ec_local = local * 4 + wave;        // this wave's count/emit chunk
+  const bool have_chunk = ec_local < n_chunks;
+  uint32_t* my_slots = slots + (size_t)(d.chunk_base + ec_local) * cap;
+  uint32_t sure = 0, filled = 0;
+#pragma unroll
+  for (int i = 0; i < HITERS; ++i) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const uint32_t key = ch.key[i][c];
+      const bool on = (ch.valid[i] >> c) & 1u;
+      const uint32_t top = key >> (kBits1 + kBits2);
+      sure += (on && top > b0) ? 1u : 0u;
+      const bool cand = on && top == b0;
+      const unsigned long long cb = __ballot(cand);
+      if (cb) {
+        if (cand) {
+          if (!s.done) atomicAdd(&lh[(key >> kBits2) & (kBins - 1)], 1u);
+          const uint32_t pos = filled + (uint32_t)__popcll(cb & ((1ull << lane) - 1ull));
+          if (pos < cap) my_slots[pos] = key & ((1u << (kBits1 + kBits2)) - 1u);
+        }
+        filled += (uint32_t)__popcll(cb);
+      }
+    }
+  }
+  sure = wave_sum_u32(sure);
+  if (lane == 0 && have_chunk) {
+    n_sure[d.chunk_base + ec_local] = sure;
+    cand_cnt[d.chunk_base + ec_local] = filled;
+  }
+  __syncthreads();
   if (s.done) return;
-  const uint32_t prefix = s.prefix;
+  uint32_t* gh = hist + (size_t)j * kHistStride + hist_offset(1);
+  for (int b = threadIdx.x; b < kBins; b += kThreads) {
+    const uint32_t v = lh[b];
+    if (v) atomicAdd(&gh[b], v);
+  }
+}
+
+// Last digit level, from the slots.  One workgroup per count/emit chunk, one thread per slot
+// entry; a chunk whose candidates overflowed its slots is read from the segment instead.
+template <int ITERS, bool FUSED>
+__global__ __launch_bounds__(kThreads) void slot_hist2_kernel(
+    const float* __restrict__ g, const SegDesc* __restrict__ seg, SegState* __restrict__ st, int m,
+    uint32_t* __restrict__ hist, const uint32_t* __restrict__ cand_cnt,
+    const uint32_t* __restrict__ slots, uint32_t cap) {
+  constexpr int kBins = 1 << kBits2;
+  __shared__ uint32_t lh[kBins];
+  __shared__ uint32_t fl[kWaves + 8];
+  const int j = seg_of_chunk(seg, m, blockIdx.x);
+  const SegDesc d = seg[j];
+  const uint32_t local = blockIdx.x - d.chunk_base;
+  const SegState s = state_after<2, FUSED>(st, m, j, hist, local == 0, fl);
+  if (s.done) return;
+  const uint32_t n = cand_cnt[blockIdx.x];
+  if (n == 0) return;
+  uint32_t* gh = hist + (size_t)j * kHistStride + hist_offset(2);
+  const uint32_t want = s.prefix & ((1u << kBits1) - 1u);  // second digit of the threshold
+  if (n <= cap) {
+    const bool on = threadIdx.x < n;
+    const uint32_t e = on ? slots[(size_t)blockIdx.x * cap + threadIdx.x] : 0u;
+    bool live = on && (e >> kBits2) == want;
+    const uint32_t digit = e & (kBins - 1);
+    // equal digits are common (rounded gradients): one atomic per distinct digit and wave
+    unsigned long long act = __ballot(live);
+    while (act) {
+      const int leader = __ffsll((long long)act) - 1;
+      const uint32_t dl = (uint32_t)__builtin_amdgcn_readlane((int)digit, leader);
+      const unsigned long long same = __ballot(live && digit == dl);
+      if ((int)(threadIdx.x & 63) == leader) atomicAdd(&gh[dl], (uint32_t)__popcll(same));
+      if (live && digit == dl) live = false;
+      act &= ~same;
+    }
+    return;
+  }
   for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
   __syncthreads();
   Chunk<ITERS> ch;
@@ -478,32 +607,10 @@ __global__ __launch_bounds__(kThreads) void hist_kernel(const float* __restrict_
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       const uint32_t key = ch.key[i][c];
-      bool on = (ch.valid[i] >> c) & 1u;
-      if (LEVEL > 0) on = on && ((key >> (kShift + kBits)) == prefix);
-      const uint32_t digit = (key >> kShift) & (kBins - 1);
-      if (LEVEL == 0) {
-        // Gradients cluster in few exponent buckets: let the lanes that share the first
-        // active lane's digit add once, the rest add individually.
-        const unsigned long long act = __ballot(on);
-        if (act) {
-          const int leader = __ffsll((long long)act) - 1;
-          const uint32_t dl = (uint32_t)__builtin_amdgcn_readlane((int)digit, leader);
-          const unsigned long long same = __ballot(on && digit == dl);
-          if (on) {
-            if (digit == dl) {
-              if ((int)(threadIdx.x & 63) == leader) atomicAdd(&lh[dl], (uint32_t)__popcll(same));
-            } else {
-              atomicAdd(&lh[digit], 1u);
-            }
-          }
-        }
-      } else {
-        if (on) atomicAdd(&lh[digit], 1u);
-      }
+      if (((ch.valid[i] >> c) & 1u) && (key >> kBits2) == s.prefix) atomicAdd(&lh[key & (kBins - 1)], 1u);
     }
   }
   __syncthreads();
-  uint32_t* gh = hist + (size_t)j * kHistStride + hist_offset(LEVEL);
   for (int b = threadIdx.x; b < kBins; b += kThreads) {
     const uint32_t v = lh[b];
     if (v) atomicAdd(&gh[b], v);
@@ -522,100 +629,43 @@ __global__ __launch_bounds__(kThreads) void find_kernel(SegState* __restrict__ s
   if (threadIdx.x == 0) st[(size_t)(LEVEL + 1) * m + j] = s;
 }
 
-// Run by one whole workgroup: walks the chunks of segment j
-// in order.  eq_base = equal keys before the chunk; out_base = output slot of the chunk's
-// first selected entry.  Each thread handles kScanPer consecutive chunks per round.
-constexpr int kScanPer = 32;
-__device__ __forceinline__ void scan_segment(const SegDesc* __restrict__ seg,
-                                             const SegState* __restrict__ st, int m, int j,
-                                             const uint32_t* __restrict__ chunk_gt,
-                                             const uint32_t* __restrict__ chunk_eq,
-                                             uint32_t* __restrict__ out_base,
-                                             uint32_t* __restrict__ eq_base,
-                                             uint32_t* __restrict__ wsum /* 2*kWaves */) {
-  const uint32_t c0 = seg[j].chunk_base, c1 = seg[j + 1].chunk_base;
-  const uint32_t r = st[(size_t)3 * m + j].r;
-  uint32_t carry_eq = 0, carry_out = seg[j].out_off;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (uint32_t t0 = c0; t0 < c1; t0 += kThreads * kScanPer) {
-    const uint32_t base = t0 + threadIdx.x * kScanPer;
-    uint32_t gt[kScanPer], eq[kScanPer];
-    uint32_t se = 0;
-#pragma unroll
-    for (int q = 0; q < kScanPer; ++q) {
-      const bool on = base + q < c1;
-      gt[q] = on ? chunk_gt[base + q] : 0u;
-      eq[q] = on ? chunk_eq[base + q] : 0u;
-      se += eq[q];
-    }
-    uint32_t ie = se;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const uint32_t n = __shfl_up(ie, o, 64);
-      if (lane >= o) ie += n;
-    }
-    __syncthreads();
-    if (lane == 63) wsum[wave] = ie;
-    __syncthreads();
-    uint32_t eb = carry_eq + ie - se;
-    for (int w = 0; w < wave; ++w) eb += wsum[w];
-    const uint32_t tile_eq = wsum[0] + wsum[1] + wsum[2] + wsum[3];
-    uint32_t ebq[kScanPer], sel[kScanPer];
-    uint32_t ss = 0;
-#pragma unroll
-    for (int q = 0; q < kScanPer; ++q) {
-      ebq[q] = eb;
-      // ties taken from this chunk: those of rank below r
-      const uint32_t take = eb >= r ? 0u : min(eq[q], r - eb);
-      sel[q] = gt[q] + take;
-      ss += sel[q];
-      eb += eq[q];
-    }
-    uint32_t is = ss;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const uint32_t n = __shfl_up(is, o, 64);
-      if (lane >= o) is += n;
-    }
-    if (lane == 63) wsum[kWaves + wave] = is;
-    __syncthreads();
-    uint32_t ob = carry_out + is - ss;
-    for (int w = 0; w < wave; ++w) ob += wsum[kWaves + w];
-    const uint32_t tile_sel = wsum[kWaves] + wsum[kWaves + 1] + wsum[kWaves + 2] + wsum[kWaves + 3];
-#pragma unroll
-    for (int q = 0; q < kScanPer; ++q) {
-      if (base + q < c1) { out_base[base + q] = ob; eq_base[base + q] = ebq[q]; }
-      ob += sel[q];
-    }
-    carry_eq += tile_eq;
-    carry_out += tile_sel;
-  }
-}
-
-// Per chunk: how many keys exceed T and how many equal it.
+// Per count/emit chunk: how many keys exceed T and how many equal it -- from the sure count
+// and the slots of pass 2, or from the segment itself for a chunk that overflowed its slots.
+// n_sure and chunk_gt may be the same array.
 template <int ITERS, bool FUSED>
-__global__ __launch_bounds__(kThreads) void count_kernel(const float* __restrict__ g,
-                                                         const SegDesc* __restrict__ seg,
-                                                         SegState* __restrict__ st, int m,
-                                                         const uint32_t* __restrict__ hist,
-                                                         uint32_t* __restrict__ chunk_gt,
-                                                         uint32_t* __restrict__ chunk_eq) {
+__global__ __launch_bounds__(kThreads) void slot_count_kernel(
+    const float* __restrict__ g, const SegDesc* __restrict__ seg, SegState* __restrict__ st, int m,
+    const uint32_t* __restrict__ hist, const uint32_t* n_sure, const uint32_t* __restrict__ cand_cnt,
+    const uint32_t* __restrict__ slots, uint32_t cap, uint32_t* chunk_gt,
+    uint32_t* __restrict__ chunk_eq) {
   __shared__ uint32_t red[2 * kWaves];
   __shared__ uint32_t fl[kWaves + 8];
   const int j = seg_of_chunk(seg, m, blockIdx.x);
   const SegDesc d = seg[j];
   const uint32_t local = blockIdx.x - d.chunk_base;
   const uint32_t T = state_after<3, FUSED>(st, m, j, hist, local == 0, fl).T;
-  Chunk<ITERS> ch;
-  ch.load(g, d.start, (int64_t)d.start + d.size, local);
+  const uint32_t n = cand_cnt[blockIdx.x];
   uint32_t gt = 0, eq = 0;
+  if (n <= cap) {
+    // every candidate shares T's top digit, so comparing the low 20 bits compares the keys
+    const uint32_t t_low = T & ((1u << (kBits1 + kBits2)) - 1u);
+    if (threadIdx.x < n) {
+      const uint32_t e = slots[(size_t)blockIdx.x * cap + threadIdx.x];
+      gt = e > t_low ? 1u : 0u;
+      eq = e == t_low ? 1u : 0u;
+    }
+    if (threadIdx.x == 0) gt += n_sure[blockIdx.x];
+  } else {
+    Chunk<ITERS> ch;
+    ch.load(g, d.start, (int64_t)d.start + d.size, local);
 #pragma unroll
-  for (int i = 0; i < ITERS; ++i) {
+    for (int i = 0; i < ITERS; ++i) {
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const bool on = (ch.valid[i] >> c) & 1u;
-      gt += (on && ch.key[i][c] > T) ? 1u : 0u;
-      eq += (on && ch.key[i][c] == T) ? 1u : 0u;
+      for (int c = 0; c < 4; ++c) {
+        const bool on = (ch.valid[i] >> c) & 1u;
+        gt += (on && ch.key[i][c] > T) ? 1u : 0u;
+        eq += (on && ch.key[i][c] == T) ? 1u : 0u;
+      }
     }
   }
   gt = wave_sum_u32(gt);
@@ -631,15 +681,72 @@ __global__ __launch_bounds__(kThreads) void count_kernel(const float* __restrict
   }
 }
 
-// One workgroup per segment: chunk counts -> output positions.
-__global__ __launch_bounds__(kThreads) void scan_kernel(const SegDesc* __restrict__ seg,
-                                                        const SegState* __restrict__ st, int m,
-                                                        const uint32_t* __restrict__ chunk_gt,
-                                                        const uint32_t* __restrict__ chunk_eq,
-                                                        uint32_t* __restrict__ out_base,
-                                                        uint32_t* __restrict__ eq_base) {
-  __shared__ uint32_t wsum[2 * kWaves];
-  scan_segment(seg, st, m, blockIdx.x, chunk_gt, chunk_eq, out_base, eq_base, wsum);
+// Exclusive prefix sums of the two per-chunk count arrays over ALL chunks of the launch
+// (segment boundaries are ignored: a segment's own prefix is a difference of two entries).
+// Level 1: one workgroup per tile of kScanTile chunks writes tile-local prefixes and the tile
+// totals; level 2: one workgroup turns the tile totals into tile bases.
+constexpr int kScanPer = 8;
+constexpr int kScanTile = kThreads * kScanPer;
+
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* wsum, uint32_t& total) {
+  uint32_t inc = v;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t n = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += n;
+  }
+  __syncthreads();
+  if (lane == 63) wsum[wave] = inc;
+  __syncthreads();
+  uint32_t before = inc - v;
+  for (int w = 0; w < wave; ++w) before += wsum[w];
+  total = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+  return before;
+}
+
+__global__ __launch_bounds__(kThreads) void scan_tiles_kernel(
+    const uint32_t* __restrict__ chunk_gt, const uint32_t* __restrict__ chunk_eq, uint32_t chunks,
+    uint32_t* __restrict__ pre_gt, uint32_t* __restrict__ pre_eq, uint32_t* __restrict__ tile_gt,
+    uint32_t* __restrict__ tile_eq) {
+  __shared__ uint32_t wsum[kWaves];
+  const uint32_t base = blockIdx.x * kScanTile + threadIdx.x * kScanPer;
+  uint32_t g[kScanPer], e[kScanPer], sg = 0, se = 0;
+#pragma unroll
+  for (int q = 0; q < kScanPer; ++q) {
+    const bool on = base + q < chunks;
+    g[q] = on ? chunk_gt[base + q] : 0u;
+    e[q] = on ? chunk_eq[base + q] : 0u;
+    sg += g[q];
+    se += e[q];
+  }
+  uint32_t tg, te;
+  uint32_t bg = block_excl_scan(sg, wsum, tg);
+  uint32_t be = block_excl_scan(se, wsum, te);
+#pragma unroll
+  for (int q = 0; q < kScanPer; ++q) {
+    if (base + q < chunks) { pre_gt[base + q] = bg; pre_eq[base + q] = be; }
+    bg += g[q];
+    be += e[q];
+  }
+  if (threadIdx.x == 0) { tile_gt[blockIdx.x] = tg; tile_eq[blockIdx.x] = te; }
+}
+
+__global__ __launch_bounds__(kThreads) void scan_tops_kernel(uint32_t* __restrict__ tile_gt,
+                                                             uint32_t* __restrict__ tile_eq,
+                                                             uint32_t tiles) {
+  __shared__ uint32_t wsum[kWaves];
+  uint32_t carry_g = 0, carry_e = 0;
+  for (uint32_t t0 = 0; t0 < tiles; t0 += kThreads) {
+    const uint32_t t = t0 + threadIdx.x;
+    const uint32_t vg = t < tiles ? tile_gt[t] : 0u, ve = t < tiles ? tile_eq[t] : 0u;
+    uint32_t tg, te;
+    const uint32_t bg = block_excl_scan(vg, wsum, tg);
+    const uint32_t be = block_excl_scan(ve, wsum, te);
+    if (t < tiles) { tile_gt[t] = carry_g + bg; tile_eq[t] = carry_e + be; }
+    carry_g += tg;
+    carry_e += te;
+  }
 }
 
 // Exclusive prefix over the wavefront of a per-lane count in [0, 7], by three ballots.
@@ -652,15 +759,17 @@ __device__ __forceinline__ uint32_t wave_excl_small(uint32_t cnt, uint32_t& tota
          4u * (uint32_t)__popcll(b2 & below);
 }
 
-// Ordered compaction of one chunk.  SCAN_HERE: the workgroup sums the counts of the chunks
-// that precede it in its segment itself (ties are granted in index order until the quota r is
-// used up, so the ties taken before this chunk are min(r, equal keys before it)); used when
-// every segment is short enough for that to be cheaper than a separate scan launch.
+// Ordered compaction of one chunk.  Ties are granted in index order until the quota r is used
+// up, so a chunk's first output slot is  out_off + (keys > T before it) + min(r, keys == T
+// before it)  within its segment.  SCAN_HERE: the workgroup sums the counts of the preceding
+// chunks of its segment itself -- cheaper than separate scan launches when every segment is
+// short; otherwise the prefixes come from scan_tiles_kernel / scan_tops_kernel.
 template <int ITERS, bool SCAN_HERE>
 __global__ __launch_bounds__(kThreads) void emit_kernel(
     const float* __restrict__ g, const SegDesc* __restrict__ seg, const SegState* __restrict__ st,
     int m, const uint32_t* __restrict__ chunk_gt, const uint32_t* __restrict__ chunk_eq,
-    const uint32_t* __restrict__ out_base, const uint32_t* __restrict__ eq_base,
+    const uint32_t* __restrict__ pre_gt, const uint32_t* __restrict__ pre_eq,
+    const uint32_t* __restrict__ tile_gt, const uint32_t* __restrict__ tile_eq,
     int32_t* __restrict__ idx_out, float* __restrict__ val_out) {
   __shared__ uint32_t wtot[2][kWaves];
   const int j = seg_of_chunk(seg, m, blockIdx.x);
@@ -682,8 +791,11 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(
     ob = d.out_off + gt_before + min(r, eb);
     __syncthreads();
   } else {
-    eb = eq_base[blockIdx.x];
-    ob = out_base[blockIdx.x];
+    // global prefixes (tile base + tile-local); the segment's own prefix is a difference
+    const uint32_t c = blockIdx.x, c0 = d.chunk_base;
+    const uint32_t gt_before = (tile_gt[c / kScanTile] + pre_gt[c]) - (tile_gt[c0 / kScanTile] + pre_gt[c0]);
+    eb = (tile_eq[c / kScanTile] + pre_eq[c]) - (tile_eq[c0 / kScanTile] + pre_eq[c0]);
+    ob = d.out_off + gt_before + min(r, eb);
   }
   const uint32_t ceq = chunk_eq[blockIdx.x];
   // 0: none of the chunk's ties is taken, 1: all are, 2: the quota ends inside this chunk
@@ -778,21 +890,26 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 #ifndef DEFT_SEL_ITERS_LARGE
 #define DEFT_SEL_ITERS_LARGE 8
 #endif
-#ifndef DEFT_HIST_ITERS_SMALL
-#define DEFT_HIST_ITERS_SMALL 16
-#endif
-#ifndef DEFT_HIST_ITERS_LARGE
-#define DEFT_HIST_ITERS_LARGE 32
-#endif
 inline int chunk_iters_for(int64_t elems) {
   return elems > (int64_t(1) << 25) ? DEFT_SEL_ITERS_LARGE : DEFT_SEL_ITERS_SMALL;
 }
 
 struct SelectLayout {
-  size_t seg, st, hist, cgt, ceq, obase, ebase, total;
+  size_t seg, st, hist, cgt, ceq, obase, ebase, tgt, teq, ccnt, slots, total;
 };
 
-SelectLayout select_layout(int64_t m, uint64_t chunks) {
+constexpr uint32_t kMaxSlotCap = kThreads;  // one thread per slot entry in the slot kernels
+
+// Slots per count/emit chunk: about four times the candidates an average chunk should hold
+// (candidates are about as many as the selected entries), within [32, kMaxSlotCap].
+inline uint32_t slot_cap_for(uint64_t total_k, uint64_t share, uint32_t chunk_elems) {
+  const double expect = 4.0 * (double)chunk_elems * (double)total_k / (double)std::max<uint64_t>(share, 1);
+  uint32_t cap = 32;
+  while (cap < kMaxSlotCap && (double)cap < expect) cap *= 2;
+  return cap;
+}
+
+SelectLayout select_layout(int64_t m, uint64_t chunks, uint32_t cap = kMaxSlotCap) {
   SelectLayout w;
   size_t o = 0;
   w.seg = o;   o = align_up(o + sizeof(SegDesc) * (size_t)(m + 1), 256);
@@ -802,6 +919,10 @@ SelectLayout select_layout(int64_t m, uint64_t chunks) {
   w.ceq = o;   o = align_up(o + sizeof(uint32_t) * chunks, 256);
   w.obase = o; o = align_up(o + sizeof(uint32_t) * chunks, 256);
   w.ebase = o; o = align_up(o + sizeof(uint32_t) * chunks, 256);
+  w.tgt = o;   o = align_up(o + sizeof(uint32_t) * (chunks / kScanTile + 1), 256);
+  w.teq = o;   o = align_up(o + sizeof(uint32_t) * (chunks / kScanTile + 1), 256);
+  w.ccnt = o;  o = align_up(o + sizeof(uint32_t) * chunks, 256);
+  w.slots = o; o = align_up(o + sizeof(uint32_t) * chunks * cap, 256);
   w.total = o;
   return w;
 }
@@ -820,29 +941,33 @@ inline uint64_t max_chunks(int64_t elems, int64_t m) {
     if ((x) != hipSuccess) return DEFT_EHIP; \
   } while (0)
 
-// The histogram passes walk larger chunks (HITERS) than the count/emit passes (ITERS): a
+// The two histogram passes walk chunks four times as large as the count/emit chunks: a
 // histogram workgroup ends by merging up to 2048 bins into the segment's histogram with global
 // atomics, a fixed cost that wants amortising; count/emit have no such tail and balance better
-// with small chunks.
-template <int ITERS, int HITERS, bool FUSED>
+// with small chunks.  Each wavefront of a histogram workgroup covers one count/emit chunk.
+template <int ITERS, bool FUSED>
 int launch_select(const float* g, const SegDesc* seg, SegState* st, int m, uint32_t chunks,
                   uint32_t hchunks, uint32_t* hist, uint32_t* cgt, uint32_t* ceq, uint32_t* obase,
-                  uint32_t* ebase, bool scan_in_emit, int32_t* idx_out, float* val_out,
-                  hipStream_t s) {
-  hist_kernel<HITERS, 0, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, st, m, hist);
+                  uint32_t* ebase, uint32_t* tgt, uint32_t* teq, uint32_t* ccnt, uint32_t* slots,
+                  uint32_t cap, bool scan_in_emit,
+                  int32_t* idx_out, float* val_out, hipStream_t s) {
+  hist0_kernel<4 * ITERS, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, m, hist);
   if (!FUSED) find_kernel<0><<<m, kThreads, 0, s>>>(st, m, hist);
-  hist_kernel<HITERS, 1, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, st, m, hist);
+  pass2_kernel<ITERS, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, st, m, hist, cgt, ccnt, slots, cap);
   if (!FUSED) find_kernel<1><<<m, kThreads, 0, s>>>(st, m, hist);
-  hist_kernel<HITERS, 2, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, st, m, hist);
+  slot_hist2_kernel<ITERS, FUSED><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist, ccnt, slots, cap);
   if (!FUSED) find_kernel<2><<<m, kThreads, 0, s>>>(st, m, hist);
-  count_kernel<ITERS, FUSED><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist, cgt, ceq);
+  slot_count_kernel<ITERS, FUSED><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist, cgt, ccnt, slots,
+                                                             cap, cgt, ceq);
   if (scan_in_emit) {
-    emit_kernel<ITERS, true><<<chunks, kThreads, 0, s>>>(g, seg, st, m, cgt, ceq, obase, ebase,
-                                                         idx_out, val_out);
+    emit_kernel<ITERS, true><<<chunks, kThreads, 0, s>>>(g, seg, st, m, cgt, ceq, obase, ebase, tgt,
+                                                         teq, idx_out, val_out);
   } else {
-    scan_kernel<<<m, kThreads, 0, s>>>(seg, st, m, cgt, ceq, obase, ebase);
-    emit_kernel<ITERS, false><<<chunks, kThreads, 0, s>>>(g, seg, st, m, cgt, ceq, obase, ebase,
-                                                          idx_out, val_out);
+    const uint32_t tiles = (chunks + kScanTile - 1) / kScanTile;
+    scan_tiles_kernel<<<tiles, kThreads, 0, s>>>(cgt, ceq, chunks, obase, ebase, tgt, teq);
+    scan_tops_kernel<<<1, kThreads, 0, s>>>(tgt, teq, tiles);
+    emit_kernel<ITERS, false><<<chunks, kThreads, 0, s>>>(g, seg, st, m, cgt, ceq, obase, ebase, tgt,
+                                                          teq, idx_out, val_out);
   }
   HIP_TRY(hipGetLastError());
   return DEFT_OK;
@@ -856,7 +981,7 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   const int iters = chunk_iters_for(share);
   const bool small = iters == DEFT_SEL_ITERS_SMALL;
   const uint32_t ce = (uint32_t)kThreads * 4 * iters;
-  const uint32_t hce = (uint32_t)kThreads * 4 * (small ? DEFT_HIST_ITERS_SMALL : DEFT_HIST_ITERS_LARGE);
+  const uint32_t hce = 4 * ce;
   std::vector<SegDesc> segs(segs_in);
   uint64_t chunks = 0, hchunks = 0;
   uint32_t longest = 0;  // chunks of the longest segment
@@ -871,7 +996,10 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   // every emit workgroup can afford to sum its segment's earlier chunk counts itself
   const bool scan_in_emit = longest <= 2048;
   if (chunks > max_chunks(share, m) || chunks >= (uint64_t(1) << 31)) return DEFT_EWS;
-  const SelectLayout w = select_layout(m, chunks);
+  uint64_t total_k = 0;
+  for (const auto& d : segs) total_k += d.k;
+  const uint32_t cap = slot_cap_for(total_k, (uint64_t)share, ce);
+  const SelectLayout w = select_layout(m, chunks, cap);
   if (w.total > ws_bytes) return DEFT_EWS;
   char* base = static_cast<char*>(ws);
   SegDesc* seg = reinterpret_cast<SegDesc*>(base + w.seg);
@@ -894,13 +1022,17 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   uint32_t* ceq = reinterpret_cast<uint32_t*>(base + w.ceq);
   uint32_t* ob = reinterpret_cast<uint32_t*>(base + w.obase);
   uint32_t* eb = reinterpret_cast<uint32_t*>(base + w.ebase);
+  uint32_t* tg = reinterpret_cast<uint32_t*>(base + w.tgt);
+  uint32_t* te = reinterpret_cast<uint32_t*>(base + w.teq);
+  uint32_t* cc = reinterpret_cast<uint32_t*>(base + w.ccnt);
+  uint32_t* sl = reinterpret_cast<uint32_t*>(base + w.slots);
   if (small)
-    return launch_select<DEFT_SEL_ITERS_SMALL, DEFT_HIST_ITERS_SMALL, true>(
-        g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, scan_in_emit,
-        idx_out, val_out, s);
-  return launch_select<DEFT_SEL_ITERS_LARGE, DEFT_HIST_ITERS_LARGE, false>(
-      g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, scan_in_emit,
-      idx_out, val_out, s);
+    return launch_select<DEFT_SEL_ITERS_SMALL, true>(
+        g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, tg, te, cc, sl, cap,
+        scan_in_emit, idx_out, val_out, s);
+  return launch_select<DEFT_SEL_ITERS_LARGE, false>(
+      g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, tg, te, cc, sl, cap,
+      scan_in_emit, idx_out, val_out, s);
 }
 
 }  // namespace
