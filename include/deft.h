@@ -27,6 +27,8 @@
  *     magnitudes the lower index is selected first.  Selected entries are reported in
  *     ascending index order with their original bit pattern.
  *   - Results are deterministic: the same inputs give the same bits.
+ *   - Environment: DEFT_LONG_VECTOR_ELEMS=<n> moves the element count above which the selection
+ *     uses its long-vector launch shape (default 2^25).  It changes speed only, never results.
  */
 #ifndef DEFT_H
 #define DEFT_H

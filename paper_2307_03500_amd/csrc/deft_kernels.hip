@@ -18,6 +18,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 #include <vector>
 
@@ -681,6 +682,146 @@ __global__ __launch_bounds__(kThreads) void slot_count_kernel(
   }
 }
 
+// Wave-per-chunk forms of the two slot kernels for long vectors (states precomputed by the find
+// kernels, so the four wavefronts of a workgroup may serve chunks of different segments): a
+// quarter of the workgroups, and the trivial chunks cost a wavefront instead of a workgroup.
+// Chunks that overflowed their slots are then handled by the whole workgroup, one at a time.
+template <int ITERS>
+__global__ __launch_bounds__(kThreads) void slot_hist2_wave_kernel(
+    const float* __restrict__ g, const SegDesc* __restrict__ seg, const SegState* __restrict__ st,
+    int m, uint32_t chunks, uint32_t* __restrict__ hist, const uint32_t* __restrict__ cand_cnt,
+    const uint32_t* __restrict__ slots, uint32_t cap) {
+  constexpr int kBins = 1 << kBits2;
+  __shared__ uint32_t lh[kBins];
+  __shared__ uint32_t ovf[kWaves];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t c = blockIdx.x * kWaves + wave;
+  bool over = false;
+  if (c < chunks) {
+    const int j = seg_of_chunk(seg, m, c);
+    const SegState s = st[(size_t)2 * m + j];
+    const uint32_t n = cand_cnt[c];
+    if (!s.done && n > 0) {
+      if (n > cap) {
+        over = true;
+      } else {
+        uint32_t* gh = hist + (size_t)j * kHistStride + hist_offset(2);
+        const uint32_t want = s.prefix & ((1u << kBits1) - 1u);
+        for (uint32_t r0 = 0; r0 < n; r0 += 64) {
+          const bool on = r0 + lane < n;
+          const uint32_t e = on ? slots[(size_t)c * cap + r0 + lane] : 0u;
+          bool live = on && (e >> kBits2) == want;
+          const uint32_t digit = e & (kBins - 1);
+          unsigned long long act = __ballot(live);
+          while (act) {
+            const int leader = __ffsll((long long)act) - 1;
+            const uint32_t dl = (uint32_t)__builtin_amdgcn_readlane((int)digit, leader);
+            const unsigned long long same = __ballot(live && digit == dl);
+            if (lane == leader) atomicAdd(&gh[dl], (uint32_t)__popcll(same));
+            if (live && digit == dl) live = false;
+            act &= ~same;
+          }
+        }
+      }
+    }
+  }
+  if (lane == 0) ovf[wave] = over ? 1u : 0u;
+  __syncthreads();
+  for (int q = 0; q < kWaves; ++q) {
+    if (!ovf[q]) continue;
+    const uint32_t cq = blockIdx.x * kWaves + q;
+    const int j = seg_of_chunk(seg, m, cq);
+    const SegDesc d = seg[j];
+    const uint32_t prefix = st[(size_t)2 * m + j].prefix;
+    __syncthreads();
+    for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
+    __syncthreads();
+    Chunk<ITERS> ch;
+    ch.load(g, d.start, (int64_t)d.start + d.size, cq - d.chunk_base);
+#pragma unroll
+    for (int i = 0; i < ITERS; ++i) {
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc) {
+        const uint32_t key = ch.key[i][cc];
+        if (((ch.valid[i] >> cc) & 1u) && (key >> kBits2) == prefix) atomicAdd(&lh[key & (kBins - 1)], 1u);
+      }
+    }
+    __syncthreads();
+    uint32_t* gh = hist + (size_t)j * kHistStride + hist_offset(2);
+    for (int b = threadIdx.x; b < kBins; b += kThreads) {
+      const uint32_t v = lh[b];
+      if (v) atomicAdd(&gh[b], v);
+    }
+  }
+}
+
+template <int ITERS>
+__global__ __launch_bounds__(kThreads) void slot_count_wave_kernel(
+    const float* __restrict__ g, const SegDesc* __restrict__ seg, const SegState* __restrict__ st,
+    int m, uint32_t chunks, const uint32_t* n_sure, const uint32_t* __restrict__ cand_cnt,
+    const uint32_t* __restrict__ slots, uint32_t cap, uint32_t* chunk_gt,
+    uint32_t* __restrict__ chunk_eq) {
+  __shared__ uint32_t red[2 * kWaves];
+  __shared__ uint32_t ovf[kWaves];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t c = blockIdx.x * kWaves + wave;
+  bool over = false;
+  if (c < chunks) {
+    const int j = seg_of_chunk(seg, m, c);
+    const uint32_t T = st[(size_t)3 * m + j].T;
+    const uint32_t n = cand_cnt[c];
+    if (n > cap) {
+      over = true;
+    } else {
+      const uint32_t t_low = T & ((1u << (kBits1 + kBits2)) - 1u);
+      uint32_t gt = 0, eq = 0;
+      for (uint32_t r0 = 0; r0 < n; r0 += 64) {
+        if (r0 + lane < n) {
+          const uint32_t e = slots[(size_t)c * cap + r0 + lane];
+          gt += e > t_low ? 1u : 0u;
+          eq += e == t_low ? 1u : 0u;
+        }
+      }
+      gt = wave_sum_u32(gt);
+      eq = wave_sum_u32(eq);
+      if (lane == 0) {
+        chunk_gt[c] = gt + n_sure[c];
+        chunk_eq[c] = eq;
+      }
+    }
+  }
+  if (lane == 0) ovf[wave] = over ? 1u : 0u;
+  __syncthreads();
+  for (int q = 0; q < kWaves; ++q) {
+    if (!ovf[q]) continue;
+    const uint32_t cq = blockIdx.x * kWaves + q;
+    const int j = seg_of_chunk(seg, m, cq);
+    const SegDesc d = seg[j];
+    const uint32_t T = st[(size_t)3 * m + j].T;
+    Chunk<ITERS> ch;
+    ch.load(g, d.start, (int64_t)d.start + d.size, cq - d.chunk_base);
+    uint32_t gt = 0, eq = 0;
+#pragma unroll
+    for (int i = 0; i < ITERS; ++i) {
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc) {
+        const bool on = (ch.valid[i] >> cc) & 1u;
+        gt += (on && ch.key[i][cc] > T) ? 1u : 0u;
+        eq += (on && ch.key[i][cc] == T) ? 1u : 0u;
+      }
+    }
+    gt = wave_sum_u32(gt);
+    eq = wave_sum_u32(eq);
+    __syncthreads();
+    if (lane == 0) { red[wave] = gt; red[kWaves + wave] = eq; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      chunk_gt[cq] = red[0] + red[1] + red[2] + red[3];
+      chunk_eq[cq] = red[kWaves] + red[kWaves + 1] + red[kWaves + 2] + red[kWaves + 3];
+    }
+  }
+}
+
 // Exclusive prefix sums of the two per-chunk count arrays over ALL chunks of the launch
 // (segment boundaries are ignored: a segment's own prefix is a difference of two entries).
 // Level 1: one workgroup per tile of kScanTile chunks writes tile-local prefixes and the tile
@@ -890,8 +1031,20 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 #ifndef DEFT_SEL_ITERS_LARGE
 #define DEFT_SEL_ITERS_LARGE 8
 #endif
+// Vectors above this many elements use the long-vector launch shape (larger chunks, separate
+// bucket-search kernels, wave-per-chunk slot kernels).  DEFT_LONG_VECTOR_ELEMS in the
+// environment overrides the threshold (for tests and tuning; read at every call).
+constexpr int64_t kLongVectorElems = int64_t(1) << 25;
+inline int64_t long_vector_elems() {
+  const char* e = std::getenv("DEFT_LONG_VECTOR_ELEMS");
+  if (e && *e) {
+    const long long v = std::atoll(e);
+    if (v >= 0) return (int64_t)v;
+  }
+  return kLongVectorElems;
+}
 inline int chunk_iters_for(int64_t elems) {
-  return elems > (int64_t(1) << 25) ? DEFT_SEL_ITERS_LARGE : DEFT_SEL_ITERS_SMALL;
+  return elems > long_vector_elems() ? DEFT_SEL_ITERS_LARGE : DEFT_SEL_ITERS_SMALL;
 }
 
 struct SelectLayout {
@@ -930,10 +1083,8 @@ SelectLayout select_layout(int64_t m, uint64_t chunks, uint32_t cap = kMaxSlotCa
 // Upper bound on the chunk count of any set of m segments holding at most `elems` elements
 // (the chunk size depends on the total, so the bound covers both regimes).
 inline uint64_t max_chunks(int64_t elems, int64_t m) {
-  const int64_t small_cap = int64_t(1) << 25;
-  int64_t c = std::min(elems, small_cap) / (kThreads * 4 * DEFT_SEL_ITERS_SMALL);
-  if (elems > small_cap) c = std::max(c, elems / (kThreads * 4 * DEFT_SEL_ITERS_LARGE));
-  return (uint64_t)(c + 2 * m + 1);
+  // the smaller chunk size bounds both launch shapes
+  return (uint64_t)(elems / (kThreads * 4 * DEFT_SEL_ITERS_SMALL) + 2 * m + 1);
 }
 
 #define HIP_TRY(x)                         \
@@ -955,10 +1106,18 @@ int launch_select(const float* g, const SegDesc* seg, SegState* st, int m, uint3
   if (!FUSED) find_kernel<0><<<m, kThreads, 0, s>>>(st, m, hist);
   pass2_kernel<ITERS, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, st, m, hist, cgt, ccnt, slots, cap);
   if (!FUSED) find_kernel<1><<<m, kThreads, 0, s>>>(st, m, hist);
-  slot_hist2_kernel<ITERS, FUSED><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist, ccnt, slots, cap);
-  if (!FUSED) find_kernel<2><<<m, kThreads, 0, s>>>(st, m, hist);
-  slot_count_kernel<ITERS, FUSED><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist, cgt, ccnt, slots,
-                                                             cap, cgt, ceq);
+  if (FUSED) {
+    slot_hist2_kernel<ITERS, true><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist, ccnt, slots, cap);
+    slot_count_kernel<ITERS, true><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist, cgt, ccnt, slots,
+                                                              cap, cgt, ceq);
+  } else {
+    const uint32_t wblocks = (chunks + kWaves - 1) / kWaves;
+    slot_hist2_wave_kernel<ITERS><<<wblocks, kThreads, 0, s>>>(g, seg, st, m, chunks, hist, ccnt,
+                                                              slots, cap);
+    find_kernel<2><<<m, kThreads, 0, s>>>(st, m, hist);
+    slot_count_wave_kernel<ITERS><<<wblocks, kThreads, 0, s>>>(g, seg, st, m, chunks, cgt, ccnt,
+                                                              slots, cap, cgt, ceq);
+  }
   if (scan_in_emit) {
     emit_kernel<ITERS, true><<<chunks, kThreads, 0, s>>>(g, seg, st, m, cgt, ceq, obase, ebase, tgt,
                                                          teq, idx_out, val_out);

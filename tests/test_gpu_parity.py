@@ -200,6 +200,32 @@ def test_select_unaligned_segments_and_subset(deft):
         _check_select(sel, gd, g, off, k, part)
 
 
+@pytest.mark.parametrize("n_c", [31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 300])
+def test_select_candidate_slots_boundary(deft, n_c):
+    """One count/emit chunk holds exactly n_c keys in the threshold's top-digit bucket, around
+    every possible slot capacity (32..256): the chunk is served from its slots or, one past the
+    capacity, from the segment itself; both must give the oracle's answer.  Other chunks hold
+    a few candidates each, and the tie class of the threshold spans chunks."""
+    N = 4096 * 5 + 77
+    rng = np.random.default_rng(n_c)
+    g = np.full(N, 1e-3, np.float32) * rng.choice([-1, 1], N).astype(np.float32)
+    big = rng.choice(N, 9, replace=False)
+    g[big] = 50.0                                     # sure picks, larger top digit
+    # threshold bucket: values in [1, 1.125) share the top 11 key bits
+    pos = 4096 + rng.choice(4096, n_c, replace=False)  # all inside the second chunk
+    g[pos] = (1.0 + rng.integers(0, 40, n_c) * 2.0 ** -10).astype(np.float32)  # many exact ties
+    other = np.setdiff1d(rng.choice(N, 25, replace=False), np.concatenate([pos, big]))
+    g[other] = (1.0 + rng.integers(0, 40, len(other)) * 2.0 ** -10).astype(np.float32)
+    sel = _selector(deft, [N], 1, 0.5, out_cap=N)
+    gd = torch.from_numpy(g).to(DEV)
+    off = sel.offsets.tolist()
+    n_big = int((np.abs(g) > 2).sum())
+    n_cand = int(((np.abs(g) >= 1) & (np.abs(g) < 2)).sum())
+    for k in sorted({n_big + 1, n_big + n_cand // 3, n_big + n_cand // 2, n_big + n_cand - 1,
+                     n_big + n_cand, n_big + n_cand + 5}):
+        _check_select(sel, gd, g, off, [k], [0])
+
+
 def test_select_many_small_segments(deft):
     """More segments than one descriptor batch holds, sizes 1..600, every start alignment."""
     rng = np.random.default_rng(21)
@@ -234,6 +260,32 @@ def test_select_repeatable_and_workspace_reuse(deft):
     sel.select(gd, rank=7)
     b = sel.select(gd, rank=3)
     assert ai.tolist() == b.idx.tolist() and (_bits(av) == _bits(b.val)).all()
+
+
+@pytest.fixture
+def long_vector_shape():
+    """Force the long-vector launch shape on small inputs (it changes speed only)."""
+    import os
+    os.environ["DEFT_LONG_VECTOR_ELEMS"] = "0"
+    yield
+    del os.environ["DEFT_LONG_VECTOR_ELEMS"]
+
+
+@pytest.mark.parametrize("kind", ["normal", "all_equal", "few_levels", "signed_zero", "ascending"])
+def test_select_adversarial_values_long_vector_shape(deft, long_vector_shape, kind):
+    test_select_adversarial_values(deft, kind)
+
+
+@pytest.mark.parametrize("n_c", [32, 33, 64, 65, 129, 257])
+def test_select_candidate_slots_boundary_long_vector_shape(deft, long_vector_shape, n_c):
+    test_select_candidate_slots_boundary(deft, n_c)
+
+
+def test_select_long_vector_shape_configs(deft, long_vector_shape):
+    test_select_tie_class_spanning_chunks(deft)
+    test_select_many_small_segments(deft)
+    test_deft_path_configs_all_ranks(deft, "lstm_lm")
+    test_topk_global_configs(deft, "lstm_lm")
 
 
 # ------------------------------------------------------------------------------ Alg. 1 neighbours
