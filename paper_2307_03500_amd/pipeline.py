@@ -151,3 +151,11 @@ class DeftSelector:
         B.topk_global(g, K, self.idx_out, self.val_out, self.ws)
         torch.cuda.current_stream().synchronize()
         return self.idx_out[:K].cpu().numpy(), self.val_out[:K].cpu().numpy()
+
+    def cltk(self, g: torch.Tensor, rank: int, iteration: int):
+        """Cyclic local Top-k (the comparison scheme of Sec. 1 / Sec. 3.1): the worker whose rank
+        equals iteration % n selects the conventional Top-k of its whole vector (to be broadcast
+        by the caller); every other worker selects nothing and waits.  Returns (idx, val) or None."""
+        if rank != iteration % self.n:
+            return None
+        return self.topk_global(g)

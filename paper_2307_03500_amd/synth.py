@@ -81,6 +81,18 @@ def gpt2_medium_sizes() -> List[int]:
     return s
 
 
+def ncf_sizes() -> List[int]:
+    """Neural collaborative filtering sized like MovieLens-20M (138 493 users, 26 744 items):
+    GMF embeddings of width 64, MLP embeddings of width 128, MLP 256-256-128-64, output 128-1.
+    The paper gives no NCF shapes (Table 2 names only the model); these are this build's."""
+    users, items = 138493, 26744
+    s = [users * 64, items * 64, users * 128, items * 128]
+    for a, b in ((256, 256), (256, 128), (128, 64)):
+        s += [a * b, b]
+    s += [128, 1]
+    return s
+
+
 # --------------------------------------------------------------------------------------
 # value fills
 # --------------------------------------------------------------------------------------
@@ -139,6 +151,11 @@ CONFIGS = {
                        zero_rows=(0, 10000, 650, 1000)),
     "bert_base": _Recipe(bert_base_sizes, _fill_student3, (-5.0, -1.0), 0.01, 16),
     "gpt2_medium": _Recipe(gpt2_medium_sizes, _fill_student3, (-5.0, -1.0), 0.001, 32, bf16=True),
+    # dense selection (d = 0.1, the density the paper uses for NCF in Sec. 5.2); embedding rows
+    # of inactive users/items carry no gradient: 70 % of the rows of each table are exactly 0
+    "ncf": _Recipe(ncf_sizes, _fill_laplace, (-4.0, -1.0), 0.1, 16,
+                   zero_rows=((0, 138493, 64, 41548), (1, 26744, 64, 8023),
+                              (2, 138493, 128, 41548), (3, 26744, 128, 8023))),
 }
 
 
@@ -179,11 +196,12 @@ def make(name: str, seed: int = 0, threads: Optional[int] = None) -> GradientSet
             run(j)
 
     if r.zero_rows is not None:
-        t, rows, cols, keep = r.zero_rows
-        st = int(sum(sizes[:t]))
-        perm = _rng(seed, (1 << 30) + 1, 0).permutation(rows)
-        zero = np.sort(perm[keep:])
-        g[st:st + rows * cols].reshape(rows, cols)[zero, :] = 0.0
+        specs = r.zero_rows if isinstance(r.zero_rows[0], tuple) else (r.zero_rows,)
+        for i, (t, rows, cols, keep) in enumerate(specs):
+            st = int(sum(sizes[:t]))
+            perm = _rng(seed, (1 << 30) + 1 + i, 0).permutation(rows)
+            zero = np.sort(perm[keep:])
+            g[st:st + rows * cols].reshape(rows, cols)[zero, :] = 0.0
     return GradientSet(name, sizes, g, r.d, r.n_workers, seed)
 
 

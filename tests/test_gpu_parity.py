@@ -81,7 +81,7 @@ def test_norms_deterministic_and_special_values(deft):
 
 
 # ------------------------------------------------------------------------------ selection
-@pytest.mark.parametrize("name", ["toy_mlp", "resnet18", "lstm_lm"])
+@pytest.mark.parametrize("name", ["toy_mlp", "resnet18", "lstm_lm", "ncf"])
 def test_deft_path_configs_all_ranks(deft, name):
     gs = synth.make(name, seed=0)
     sel = _selector(deft, gs.tensor_sizes, gs.n_workers, gs.d)
@@ -109,7 +109,7 @@ def test_deft_path_configs_all_ranks(deft, name):
     assert len(np.unique(allidx)) == len(allidx) == sum(o_k)
 
 
-@pytest.mark.parametrize("name", ["toy_mlp", "resnet18", "lstm_lm"])
+@pytest.mark.parametrize("name", ["toy_mlp", "resnet18", "lstm_lm", "ncf"])
 def test_topk_global_configs(deft, name):
     gs = synth.make(name, seed=0)
     sel = _selector(deft, gs.tensor_sizes, gs.n_workers, gs.d)
@@ -166,6 +166,35 @@ def test_select_adversarial_values(deft, kind):
         else:
             k = [int(rng.integers(0, s + 1)) for s in sizes]  # includes k = 0
         _check_select(sel, gd, g, off, k, part)
+
+
+def test_select_nan_ranks_above_inf(deft):
+    """NaN keys (bit patterns above infinity's) are the largest magnitudes, on both sides."""
+    rng = np.random.default_rng(8)
+    N = 30000
+    g = rng.standard_normal(N).astype(np.float32)
+    g[rng.choice(N, 7, replace=False)] = np.nan
+    g[rng.choice(N, 5, replace=False)] = -np.inf
+    u = g.view(np.uint32)
+    u[123] = 0xFFC00001  # negative quiet NaN with payload
+    sel = _selector(deft, [N], 1, 0.5, out_cap=N)
+    gd = torch.from_numpy(g).to(DEV)
+    for k in (1, 7, 8, 12, 13, 100):
+        _check_select(sel, gd, g, sel.offsets.tolist(), [k], [0])
+
+
+def test_cltk_leader_only(deft):
+    gs = synth.make("toy_mlp", seed=4)
+    sel = _selector(deft, gs.tensor_sizes, gs.n_workers, gs.d)
+    gd = torch.from_numpy(gs.g).to(DEV)
+    oi, ov = O.topk_global(gs.g, O.total_k(gs.N, gs.d))
+    for it in (0, 1, 5, 7):
+        for r in range(gs.n_workers):
+            out = sel.cltk(gd, r, it)
+            if r == it % gs.n_workers:
+                assert out[0].tolist() == oi.tolist() and (_bits(out[1]) == _bits(ov)).all()
+            else:
+                assert out is None
 
 
 def test_select_tie_class_spanning_chunks(deft):
