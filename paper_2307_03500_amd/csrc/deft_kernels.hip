@@ -456,7 +456,8 @@ __device__ __forceinline__ SegState state_after(SegState* __restrict__ st, int m
 template <int HITERS, bool FUSED>
 __global__ __launch_bounds__(kThreads) void hist0_kernel(const float* __restrict__ g,
                                                          const SegDesc* __restrict__ seg, int m,
-                                                         uint32_t* __restrict__ hist) {
+                                                         uint32_t* __restrict__ hist,
+                                                         uint32_t* __restrict__ hmax) {
   constexpr int kBins = 1 << kBits0;
   constexpr int kShift = kBits1 + kBits2;
   __shared__ uint32_t lh[kBins];
@@ -491,10 +492,16 @@ __global__ __launch_bounds__(kThreads) void hist0_kernel(const float* __restrict
   }
   __syncthreads();
   uint32_t* gh = hist + (size_t)j * kHistStride + hist_offset(0);
+  int top_bin = 0;
   for (int b = threadIdx.x; b < kBins; b += kThreads) {
     const uint32_t v = lh[b];
-    if (v) atomicAdd(&gh[b], v);
+    if (v) { atomicAdd(&gh[b], v); top_bin = b; }
   }
+  // largest top digit present in the chunk (hmax starts at 0): pass 2 skips chunks that cannot
+  // hold a candidate
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) top_bin = max(top_bin, __shfl_down(top_bin, o, 64));
+  if ((threadIdx.x & 63) == 0 && top_bin > 0) atomicMax(&hmax[blockIdx.x], (uint32_t)top_bin);
 }
 
 // Pass 2 of 3 over the segment.  The top digit b0 of the threshold is known.  Keys with a
@@ -508,8 +515,8 @@ __global__ __launch_bounds__(kThreads) void hist0_kernel(const float* __restrict
 template <int ITERS, bool FUSED>
 __global__ __launch_bounds__(kThreads) void pass2_kernel(
     const float* __restrict__ g, const SegDesc* __restrict__ seg, SegState* __restrict__ st, int m,
-    uint32_t* __restrict__ hist, uint32_t* __restrict__ n_sure, uint32_t* __restrict__ cand_cnt,
-    uint32_t* __restrict__ slots, uint32_t cap) {
+    uint32_t* __restrict__ hist, const uint32_t* __restrict__ hmax, uint32_t* __restrict__ n_sure,
+    uint32_t* __restrict__ cand_cnt, uint32_t* __restrict__ slots, uint32_t cap) {
   constexpr int HITERS = 4 * ITERS;
   constexpr int kBins = 1 << kBits1;
   __shared__ uint32_t lh[kBins];
@@ -519,14 +526,22 @@ __global__ __launch_bounds__(kThreads) void pass2_kernel(
   const uint32_t local = blockIdx.x - d.hchunk_base;
   const SegState s = state_after<1, FUSED>(st, m, j, hist, local == 0, fl);
   const uint32_t b0 = s.done ? (s.T >> (kBits1 + kBits2)) : s.prefix;
-  for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
-  __syncthreads();
-  Chunk<HITERS> ch;
-  ch.load(g, d.start, (int64_t)d.start + d.size, local);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint32_t n_chunks = seg[j + 1].chunk_base - d.chunk_base;
   const uint32_t ec_local = local * 4 + wave;        // this wave's count/emit chunk
   const bool have_chunk = ec_local < n_chunks;
+  if (hmax[blockIdx.x] < b0) {
+    // every key here lies below the threshold's bucket: nothing sure, no candidate, no read
+    if (lane == 0 && have_chunk) {
+      n_sure[d.chunk_base + ec_local] = 0;
+      cand_cnt[d.chunk_base + ec_local] = 0;
+    }
+    return;
+  }
+  for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
+  __syncthreads();
+  Chunk<HITERS> ch;
+  ch.load(g, d.start, (int64_t)d.start + d.size, local);
   uint32_t* my_slots = slots + (size_t)(d.chunk_base + ec_local) * cap;
   uint32_t sure = 0, filled = 0;
 #pragma unroll
@@ -916,6 +931,10 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(
   const int j = seg_of_chunk(seg, m, blockIdx.x);
   const SegDesc d = seg[j];
   const uint32_t T = st[(size_t)3 * m + j].T, r = st[(size_t)3 * m + j].r;
+  // a chunk that holds nothing to select is not read at all (layers whose magnitudes lie
+  // below the threshold -- most of the vector for the conventional Top-k)
+  const uint32_t cgt = chunk_gt[blockIdx.x], ceq = chunk_eq[blockIdx.x];
+  if (cgt == 0 && ceq == 0) return;
   uint32_t eb, ob;
   if (SCAN_HERE) {
     uint32_t sg = 0, se = 0;
@@ -938,7 +957,7 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(
     eb = (tile_eq[c / kScanTile] + pre_eq[c]) - (tile_eq[c0 / kScanTile] + pre_eq[c0]);
     ob = d.out_off + gt_before + min(r, eb);
   }
-  const uint32_t ceq = chunk_eq[blockIdx.x];
+  if (cgt == 0 && eb >= r) return;  // only ties here, and the quota was used up before them
   // 0: none of the chunk's ties is taken, 1: all are, 2: the quota ends inside this chunk
   const int mode = (eb >= r) ? 0 : ((r - eb >= ceq) ? 1 : 2);
   Chunk<ITERS> ch;
@@ -1048,7 +1067,7 @@ inline int chunk_iters_for(int64_t elems) {
 }
 
 struct SelectLayout {
-  size_t seg, st, hist, cgt, ceq, obase, ebase, tgt, teq, ccnt, slots, total;
+  size_t seg, st, hist, cgt, ceq, obase, ebase, tgt, teq, ccnt, hmax, slots, total;
 };
 
 constexpr uint32_t kMaxSlotCap = kThreads;  // one thread per slot entry in the slot kernels
@@ -1067,7 +1086,8 @@ SelectLayout select_layout(int64_t m, uint64_t chunks, uint32_t cap = kMaxSlotCa
   size_t o = 0;
   w.seg = o;   o = align_up(o + sizeof(SegDesc) * (size_t)(m + 1), 256);
   w.st = o;    o = align_up(o + sizeof(SegState) * 4 * (size_t)m, 256);  // state after 0..3 levels
-  w.hist = o;  o = align_up(o + sizeof(uint32_t) * kHistStride * (size_t)m, 256);
+  w.hist = o;  o = o + sizeof(uint32_t) * kHistStride * (size_t)m;  // hmax follows: zeroed together
+  w.hmax = o;  o = align_up(o + sizeof(uint32_t) * (chunks / 4 + 2 * (size_t)m + 1), 256);
   w.cgt = o;   o = align_up(o + sizeof(uint32_t) * chunks, 256);
   w.ceq = o;   o = align_up(o + sizeof(uint32_t) * chunks, 256);
   w.obase = o; o = align_up(o + sizeof(uint32_t) * chunks, 256);
@@ -1099,12 +1119,14 @@ inline uint64_t max_chunks(int64_t elems, int64_t m) {
 template <int ITERS, bool FUSED>
 int launch_select(const float* g, const SegDesc* seg, SegState* st, int m, uint32_t chunks,
                   uint32_t hchunks, uint32_t* hist, uint32_t* cgt, uint32_t* ceq, uint32_t* obase,
-                  uint32_t* ebase, uint32_t* tgt, uint32_t* teq, uint32_t* ccnt, uint32_t* slots,
+                  uint32_t* ebase, uint32_t* tgt, uint32_t* teq, uint32_t* ccnt, uint32_t* hmax,
+                  uint32_t* slots,
                   uint32_t cap, bool scan_in_emit,
                   int32_t* idx_out, float* val_out, hipStream_t s) {
-  hist0_kernel<4 * ITERS, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, m, hist);
+  hist0_kernel<4 * ITERS, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, m, hist, hmax);
   if (!FUSED) find_kernel<0><<<m, kThreads, 0, s>>>(st, m, hist);
-  pass2_kernel<ITERS, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, st, m, hist, cgt, ccnt, slots, cap);
+  pass2_kernel<ITERS, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, st, m, hist, hmax, cgt, ccnt, slots,
+                                                          cap);
   if (!FUSED) find_kernel<1><<<m, kThreads, 0, s>>>(st, m, hist);
   if (FUSED) {
     slot_hist2_kernel<ITERS, true><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist, ccnt, slots, cap);
@@ -1164,7 +1186,7 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   SegDesc* seg = reinterpret_cast<SegDesc*>(base + w.seg);
   SegState* st = reinterpret_cast<SegState*>(base + w.st);
   uint32_t* hist = reinterpret_cast<uint32_t*>(base + w.hist);
-  const size_t nzero = (size_t)kHistStride * m;
+  const size_t nzero = (size_t)kHistStride * m + hchunks;  // histograms and the per-chunk maxima
   const unsigned setup_blocks = (unsigned)std::min<size_t>((nzero + 4 * kThreads - 1) / (4 * kThreads), 256);
   for (int first = 0; first < m; first += kSegBatch) {
     SegBatch b;
@@ -1184,13 +1206,14 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   uint32_t* tg = reinterpret_cast<uint32_t*>(base + w.tgt);
   uint32_t* te = reinterpret_cast<uint32_t*>(base + w.teq);
   uint32_t* cc = reinterpret_cast<uint32_t*>(base + w.ccnt);
+  uint32_t* hm = reinterpret_cast<uint32_t*>(base + w.hmax);
   uint32_t* sl = reinterpret_cast<uint32_t*>(base + w.slots);
   if (small)
     return launch_select<DEFT_SEL_ITERS_SMALL, true>(
-        g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, tg, te, cc, sl, cap,
+        g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, tg, te, cc, hm, sl, cap,
         scan_in_emit, idx_out, val_out, s);
   return launch_select<DEFT_SEL_ITERS_LARGE, false>(
-      g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, tg, te, cc, sl, cap,
+      g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, tg, te, cc, hm, sl, cap,
       scan_in_emit, idx_out, val_out, s);
 }
 
