@@ -5,10 +5,17 @@
 // Both are streaming passes bound by HBM bandwidth: 16-byte loads, 64-lane wavefront
 // reductions/ballots, per-workgroup LDS histograms, no matrix instructions.
 //
-// Selection = exact radix select on the 31-bit key (bits & 0x7fffffff), three digit levels of
-// 11/10/10 bits, then an ordered compaction:
-//   hist(level) -> find(level)   x3     threshold key T and tie quota r per segment
-//   count -> scan -> emit               per-chunk counts, exclusive prefix, ordered write
+// Selection = exact radix select on the 31-bit key (bits & 0x7fffffff), digit levels of
+// 11/10/10 bits, in three passes over a segment, then an ordered compaction:
+//   hist0        pass 1: histogram of the top digit; largest top digit of every chunk
+//   pass2        pass 2: counts keys above the threshold's top-digit bucket, histograms the
+//                bucket's keys on the second digit and parks their low 20 bits in per-chunk slots
+//   slot_hist2   third digit level, from the slots
+//   slot_count   per-chunk counts of keys > T and == T, from the slots
+//   emit         pass 3: ordered (index, value) write
+// The bucket search between levels runs inside the next kernel (short vectors) or as a
+// one-workgroup-per-segment kernel (long vectors).  Passes 2 and 3 skip chunks that cannot
+// hold a selected entry.
 // An element is selected iff key > T, or key == T and fewer than r equal keys precede it in
 // its segment.  Every pass walks the segments in fixed-size chunks; a chunk never spans two
 // segments, so small layers simply own short chunks and large layers are split over many
