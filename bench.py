@@ -282,10 +282,11 @@ def main():
                 "bytes_per_launch": 4 * N, "avg_launch_ms": norm_avg_ms}
 
     out = {
-        "metric": "DEFT selection (norms + plan + segmented Top-k), GB/s scanned per worker share",
+        "metric": "selection ms/iter & GB/s scanned (norms+top-k) vs HBM peak, per worker share",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32 data, u32 key compares, f64 norm accumulation",
+        "vs_baseline": None, "dtype": "f64",
+        "dtype_note": "fp32 data; norm pass accumulates in f64; selection compares u32 keys",
         "data": "synthetic",
         "config": {"workload": f"{args.config}-shaped gradient set, seed {args.seed}, worker "
                                f"{rank} of {n}, d={gs.d}",
