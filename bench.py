@@ -117,6 +117,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one device-to-device copy of the vector (4N read + 4N written), "
                          "the known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--lib", default="",
+                    help="path of another build of libdeft.so to load (measurement variants "
+                         "compiled with a -D switch)")
     ap.add_argument("--sweep-workers", default="",
                     help="comma-separated worker counts: print the selection-speedup curve "
                          "(the analogue of the paper's Fig. 9) instead of the benchmark line")
@@ -130,6 +133,8 @@ def main():
     from paper_2307_03500_amd import binding as B
     from paper_2307_03500_amd import pipeline, synth
 
+    if args.lib:
+        B.LIB_PATH = os.path.abspath(args.lib)
     if not os.path.exists(B.LIB_PATH):
         import __graft_entry__
         __graft_entry__.build()
