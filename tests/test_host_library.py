@@ -25,6 +25,22 @@ def test_library_exports_every_declared_symbol(deft):
     assert declared == set(deft.SIGNATURES)
 
 
+def test_header_is_plain_c_and_library_links_from_c(deft, tmp_path):
+    """include/deft.h compiles as strict C99 and a C program can call the library directly."""
+    import shutil
+    import subprocess
+    cc = shutil.which("gcc") or shutil.which("cc")
+    if cc is None:
+        pytest.skip("no C compiler")
+    exe = str(tmp_path / "c_abi_check")
+    libdir = os.path.dirname(deft.LIB_PATH)
+    subprocess.run([cc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror",
+                    "-I", os.path.join(ROOT, "include"), os.path.join(ROOT, "tests", "c_abi_check.c"),
+                    "-L", libdir, "-l:libdeft.so", "-Wl,-rpath," + libdir, "-o", exe], check=True)
+    out = subprocess.run([exe], check=True, capture_output=True, text=True)
+    assert "c abi ok" in out.stdout
+
+
 @pytest.mark.parametrize("name", list(synth.CONFIGS))
 def test_partition_matches_oracle_on_configs(deft, name):
     sizes = synth.tensor_sizes(name)
