@@ -440,3 +440,43 @@ def test_full_size_configs(deft, name, ranks):
             assert (idx == o_idx).all() and (_bits(val) == _bits(o_val)).all()
     gi, gv = sel.topk_global(gd)
     _verify_topk_by_threshold(gs.g, gi.astype(np.int64), gv, 0, gs.N, sel.K)
+
+
+def test_maximum_vector_length(deft):
+    """N = 2^31 - 5 (the largest index still fits int32; odd length, ragged tail): a vector of
+    zeros with planted values, so the expected answer is known by construction -- the planted
+    entries by magnitude, then the lowest-index zeros.  Exercises 64-bit offsets, the largest
+    chunk counts and indices just below 2^31."""
+    N = 2 ** 31 - 5
+    g = torch.zeros(N, dtype=torch.float32, device=DEV)
+    planted = {0: 3.0, 1: -0.5, 4095: 7.0, 4096: -7.5, 8191: 1.0, 8192: 2.0, 2 ** 30 + 3: -9.0,
+               2 ** 31 - 4096 - 7: 4.0, N - 2: 6.0, N - 1: -8.0}
+    pos = torch.tensor(list(planted), dtype=torch.int64, device=DEV)
+    g[pos] = torch.tensor(list(planted.values()), dtype=torch.float32, device=DEV)
+    sizes = [2 ** 30 + 1, 2 ** 30 - 6]  # two layers, the boundary at an odd position
+    assert sum(sizes) == N
+    sel = pipeline.DeftSelector(sizes, 1, 1e-8, DEV, out_cap=64)
+    # norms: exact sums of the planted squares per layer
+    got = sel.norms(g)
+    want = [np.sqrt(sum(v * v for p, v in planted.items() if p < sizes[0])),
+            np.sqrt(sum(v * v for p, v in planted.items() if p >= sizes[0]))]
+    assert got.tolist() == want
+    # conventional Top-k: all planted entries plus the three lowest-index zeros
+    K = len(planted) + 3
+    gi, gv = sel.topk_global(g, K)
+    zeros = [i for i in range(20) if i not in planted][:3]
+    exp = sorted(list(planted) + zeros)
+    assert gi.tolist() == exp
+    assert gv.tolist() == [planted.get(i, 0.0) for i in exp]
+    # layer-wise: 4 from the first layer, 5 from the second (one more than its planted entries)
+    k = np.array([4, 5], np.int64)
+    seg, idx_dev, val_dev = sel.select_with_plan(g, k, np.array([1, 0], np.int32))
+    torch.cuda.synchronize()
+    first = sorted((p for p in planted if p < sizes[0]), key=lambda p: (-abs(planted[p]), p))[:4]
+    second = [p for p in planted if p >= sizes[0]] + [sizes[0]]  # + the layer's first zero
+    assert seg.tolist() == [0, 5, 9]
+    assert idx_dev.cpu().tolist() == sorted(second) + sorted(first)
+    # one element more does not fit 32-bit indices
+    assert deft.deft_check_layout([0, 2 ** 31], 2 ** 31) == deft.DEFT_ERANGE
+    del g
+    torch.cuda.empty_cache()
