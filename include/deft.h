@@ -20,6 +20,8 @@
  *     default stream).  They never synchronise; outputs are valid once the caller has
  *     synchronised the stream.  The workspace must stay untouched until then.  Host
  *     arrays passed to a device call are consumed before it returns.
+ *     A device call launches kernels only (no allocation, no memset, no copy), so it may be
+ *     recorded in a HIP graph; the graph then replays the plan (k, layer list) it was given.
  *   - Every call returns a status: DEFT_OK (0) or a negative code.  On DEFT_EINVAL,
  *     DEFT_ERANGE, DEFT_EWS and DEFT_ECAP nothing has been written or enqueued.
  *   - Magnitudes are compared through the integer key (bit pattern & 0x7fffffff): exact

@@ -480,3 +480,41 @@ def test_maximum_vector_length(deft):
     assert deft.deft_check_layout([0, 2 ** 31], 2 ** 31) == deft.DEFT_ERANGE
     del g
     torch.cuda.empty_cache()
+
+
+def test_calls_can_be_captured_in_a_hip_graph(deft):
+    """The device entry points only launch kernels on the given stream (no allocation, no
+    memset, no synchronisation), so a caller may record them in a HIP graph.  The graph is
+    replayed several times with eager work and synchronisations in between, on changing
+    data, and every replay is compared with the eager result."""
+    gs = synth.make("resnet18", seed=5)
+    sel = _selector(deft, gs.tensor_sizes, gs.n_workers, gs.d)
+    gd = torch.from_numpy(gs.g).to(DEV)
+    res = sel.select(gd, rank=2)                       # eager: fixes the plan (k, layers)
+    k, mine = res.k.copy(), res.my_layers.copy()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        deft.deft_layer_norms(gd, sel.offsets_dev, sel.sumsq_host, sel.ws, stream=torch.cuda.current_stream())
+        seg = deft.deft_select(gd, sel.offsets, k, mine, sel.idx_out, sel.val_out, sel.ws,
+                               stream=torch.cuda.current_stream())
+    kr = int(seg[-1])
+    rng = np.random.default_rng(0)
+    for rep in range(4):
+        # change the data between replays: the graph must recompute, not replay old results
+        g_host = gs.g * np.float32(1.0 + 0.25 * rep)
+        g_host[rng.integers(0, gs.N, 1000)] *= np.float32(50.0)
+        gd.copy_(torch.from_numpy(g_host))
+        sel.idx_out.zero_()                            # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        idx = sel.idx_out[:kr].cpu().numpy()
+        val = sel.val_out[:kr].cpu().numpy()
+        norms = deft.deft_norms_from_sumsq(sel.sumsq_host.numpy())
+        off = sel.offsets.tolist()
+        o_idx, o_val, _ = O.select(g_host, off, k.tolist(), mine.tolist())
+        assert idx.tolist() == o_idx.tolist()
+        assert (_bits(val) == _bits(o_val)).all()
+        _check_norms(norms, O.layer_norms(g_host, off))
