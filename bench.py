@@ -104,6 +104,47 @@ def sweep_workers(args, ns):
                       "topk_global_ms": global_ms, "sweep": rows, "data": "synthetic"}))
 
 
+def sweep_density(args, ds):
+    """Selection time against the density d (the paper varies d in Sec. 5.4): a bandwidth-bound
+    radix select should not depend on k the way the n*log(k) model of Sec. 4.3 does."""
+    import torch
+    from paper_2307_03500_amd import binding as B
+    from paper_2307_03500_amd import pipeline, synth
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    gs = synth.make(args.config, seed=args.seed)
+    g = torch.from_numpy(gs.g).to(dev)
+    stream = torch.cuda.current_stream()
+    h = stream.cuda_stream
+
+    def timeit(fn, warm=3, reps=20):
+        for _ in range(warm):
+            fn()
+        stream.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        stream.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / reps
+
+    rows = []
+    for d in ds:
+        sel = pipeline.DeftSelector(gs.tensor_sizes, gs.n_workers, d, dev)
+        sel.enqueue_norms(g, h)
+        stream.synchronize()
+        per = []
+        for r in range(gs.n_workers):
+            cnt = sel.plan_host(r, 0)
+            per.append(timeit(lambda: sel.enqueue_select(g, cnt, h), warm=2, reps=10))
+        glob = timeit(lambda: B.topk_global(g, sel.K, sel.idx_out, sel.val_out, sel.ws))
+        rows.append({"d": d, "K": sel.K, "sum_k": int(sel.k_h.sum()), "select_ms_max": max(per),
+                     "select_ms_mean": sum(per) / len(per), "topk_global_ms": glob})
+        del sel
+    print(json.dumps({"metric": "selection time vs density", "config": {
+        "workload": f"{args.config}-shaped gradient set, seed {args.seed}, n={gs.n_workers}",
+        "N": gs.N}, "sweep": rows, "data": "synthetic"}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -126,6 +167,8 @@ def main():
     ap.add_argument("--sweep-workers", default="",
                     help="comma-separated worker counts: print the selection-speedup curve "
                          "(the analogue of the paper's Fig. 9) instead of the benchmark line")
+    ap.add_argument("--sweep-density", default="",
+                    help="comma-separated densities: print selection time against d")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU (one worker's share of an n-worker job); "
@@ -144,6 +187,9 @@ def main():
     B.lib()
     if args.sweep_workers:
         sweep_workers(args, [int(x) for x in args.sweep_workers.split(",")])
+        return
+    if args.sweep_density:
+        sweep_density(args, [float(x) for x in args.sweep_density.split(",")])
         return
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
