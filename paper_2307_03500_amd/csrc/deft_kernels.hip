@@ -323,10 +323,10 @@ struct Chunk {
     base = cstart + ((int64_t)wave * ITERS * 64 + lane) * 4;
     if (cstart >= s && cstart + kElems <= e) {
       // interior chunk (uniform over the workgroup): all loads in flight together
-      const uint4* __restrict__ p = reinterpret_cast<const uint4*>(g + base);
+      const v4u* __restrict__ p = reinterpret_cast<const v4u*>(g + base);
 #pragma unroll
       for (int i = 0; i < ITERS; ++i) {
-        const uint4 v = p[i * 64];
+        const v4u v = __builtin_nontemporal_load(&p[i * 64]);  // streamed: keep it out of L2's way
         raw[i][0] = v.x; raw[i][1] = v.y; raw[i][2] = v.z; raw[i][3] = v.w;
         valid[i] = 0xF;
       }
