@@ -164,6 +164,9 @@ def main():
     ap.add_argument("--lib", default="",
                     help="path of another build of libdeft.so to load (measurement variants "
                          "compiled with a -D switch)")
+    ap.add_argument("--stepwise", action="store_true",
+                    help="time the step-wise calls (deft_layer_norms, stream sync, the three host "
+                         "calls, deft_select) instead of the single deft_sparsify entry")
     ap.add_argument("--sweep-workers", default="",
                     help="comma-separated worker counts: print the selection-speedup curve "
                          "(the analogue of the paper's Fig. 9) instead of the benchmark line")
@@ -207,37 +210,49 @@ def main():
         del g2
 
     def step():
-        return sel.select(g, rank=rank, iteration=0)
+        return sel.sparsify(g, rank=rank, iteration=0)
 
     for _ in range(args.warmup):
         res = step()
     torch.cuda.synchronize()
     first_idx = res.idx.copy()  # the output buffers are reused by every later call
 
-    # ---- timed region: exactly `steps` whole-path steps, events around the two device phases
+    # ---- timed region: exactly `steps` whole-path steps, each one deft_sparsify call (norm pass
+    # -> wait for the sums -> Alg. 3 -> Alg. 4 -> Alg. 5 enqueued), with an event pair around the
+    # norm pass: the first recorded here, the second by the library right behind the norm kernels
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
-    plan_ms = []
+    for a, b in ev:  # a torch event gets its HIP handle on its first record
+        a.record(stream)
+        b.record(stream)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
+    evh = [b.cuda_event for _, b in ev]
     h = stream.cuda_stream
+    t0 = time.perf_counter()
     for s in range(args.steps):
-        e = ev[s]
-        e[0].record(stream)
-        sel.enqueue_norms(g, h)
-        e[1].record(stream)
-        stream.synchronize()
-        p0 = time.perf_counter()
-        cnt = sel.plan_host(rank, 0)
-        p1 = time.perf_counter()
-        k_r = sel.enqueue_select(g, cnt, h)
+        ev[s][0].record(stream)
+        if args.stepwise:
+            sel.enqueue_norms(g, h)
+            ev[s][1].record(stream)
+            stream.synchronize()
+            cnt = sel.plan_host(rank, 0)
+            k_r = sel.enqueue_select(g, cnt, h)
+            continue
+        cnt, k_r = sel.enqueue_sparsify(g, rank, 0, h, evh[s])
         # no sync here: the next step's norm pass queues behind this step's selection (same
-        # stream, same buffers); the host only has to wait where the method needs it, for the
-        # norms.  The K steps are bracketed by synchronisations on both sides.
-        plan_ms.append((p1 - p0) * 1e3)
+        # stream, same buffers); the host only waits where the method needs it, for the norms
+        # (inside the call).  The K steps are bracketed by synchronisations on both sides.
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     norm_ms = [e[0].elapsed_time(e[1]) for e in ev]
+
+    # host plan alone (Alg. 3 + Alg. 4 on the sums just delivered), outside the timed region
+    plan_ms = []
+    for i in range(150):
+        p0 = time.perf_counter()
+        sel.plan_host(rank, 0)
+        if i >= 50:
+            plan_ms.append((time.perf_counter() - p0) * 1e3)
 
     # selection alone (same plan), outside the timed region: event pairs around deft_select
     sev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(20)]
@@ -348,6 +363,7 @@ def main():
                    "share_layers": int(len(mine)), "S_r": S_r, "k_r": k_r,
                    "sum_k_minus_K": int(k.sum()) - K},
         "frac_of_hbm_peak": value / HBM_PEAK_GBPS,
+        "entry": "step-wise calls" if args.stepwise else "deft_sparsify",
         "parts_ms": {"norm_pass": _median(norm_ms), "host_plan": _median(plan_ms),
                      "select": _median(select_ms),
                      "sync_and_launch_overhead": ms_per_step - _median(norm_ms) - _median(plan_ms)

@@ -17,7 +17,8 @@
  *     host memory.  The caller owns every buffer.  The library allocates and frees no
  *     device memory and keeps no state between calls.
  *   - Device calls only enqueue work on `stream` (a hipStream_t passed as void*, NULL = the
- *     default stream).  They never synchronise; outputs are valid once the caller has
+ *     default stream).  They never synchronise (deft_sparsify alone waits on the host for
+ *     its own norm pass); outputs are valid once the caller has
  *     synchronised the stream.  The workspace must stay untouched until then.  Host
  *     arrays passed to a device call are consumed before it returns.
  *     A device call launches kernels only (no allocation, no memset, no copy), so it may be
@@ -198,6 +199,69 @@ int deft_accumulate_norms(const float* e_dev, const float* grad_dev, float eta, 
  */
 int deft_gather_zero(float* acc_dev, int64_t N, const int32_t* idx_dev, int64_t count,
                      float* vals_out_dev, void* stream);
+
+/*
+ * One sparsifier call (Sec. 4, opening paragraph: norms -> local k -> layer allocation ->
+ * layer-wise selection; the Sparsify() of Alg. 1) as a single entry point: the same work, in
+ * the same order and with the same results, as
+ *   deft_layer_norms -> wait for the sums -> deft_norms_from_sumsq -> deft_alloc_k ->
+ *   deft_assign_layers -> deft_select.
+ * Unlike the other device calls it BLOCKS the calling thread until the norm pass has
+ * delivered its sums (the host plan needs them) and returns with the selection enqueued on
+ * `stream`; idx/val are valid once the caller has synchronised the stream.  It waits by
+ * reading job->sumsq_pinned (every entry is set to an impossible bit pattern before the norm
+ * pass is enqueued and overwritten by it); after DEFT_SPIN_US microseconds (environment,
+ * default 20000; 0 = at once) it falls back to hipStreamSynchronize.  Not capturable in a HIP
+ * graph (it waits on the host).
+ *
+ * deft_job holds what stays the same from call to call; the caller fills it once.
+ *   N, L, n_workers, rank, d     the job (d in (0,1], rank in [0, n_workers))
+ *   offsets_host / offsets_dev   the same L+1 offsets in host and in device memory
+ *   sizes_host[L]                layer sizes (offsets[l+1] - offsets[l])
+ *   sumsq_pinned[L]              pinned host memory the device can write (hipHostMalloc);
+ *                                holds the sums of squares after the call
+ *   norms_host[L], k_host[L], owner_bin_host[L], my_layers_host[L], seg_off_host[L+1]
+ *                                outputs of the plan, as for the step-wise calls
+ *   idx_out_dev, val_out_dev, out_cap   outputs of deft_select
+ *   ws_dev, ws_bytes             scratch, >= max(deft_workspace_bytes(DEFT_OP_NORMS, N, L),
+ *                                deft_workspace_bytes(DEFT_OP_SELECT, N, L)); 16-byte aligned
+ * Per call:
+ *   g_dev              in   N floats, device, 16-byte aligned
+ *   iteration          in   rotates the bin -> worker map (Alg. 4)
+ *   norms_done_event   in   a hipEvent_t (as void*) recorded on `stream` right after the norm
+ *                           pass, or NULL
+ *   my_count_out       out  number of layers of the caller's bin
+ *   k_r_out            out  number of selected entries (= seg_off_host[my_count])
+ * Errors: those of the step-wise calls; DEFT_EHIP also if the sums never arrive.  Arguments
+ * are checked before anything is written or enqueued, except DEFT_ECAP: the sum of the k's
+ * depends on the data, so it is found after the norm pass; norms, k and the bins are then
+ * valid and no selection has been enqueued.
+ */
+typedef struct deft_job {
+  int64_t N;
+  int32_t L;
+  int32_t n_workers;
+  int32_t rank;
+  int32_t reserved; /* 0 */
+  double d;
+  const int64_t* offsets_host;
+  const int64_t* offsets_dev;
+  const int64_t* sizes_host;
+  double* sumsq_pinned;
+  double* norms_host;
+  int64_t* k_host;
+  int32_t* owner_bin_host;
+  int32_t* my_layers_host;
+  int64_t* seg_off_host;
+  int32_t* idx_out_dev;
+  float* val_out_dev;
+  int64_t out_cap;
+  void* ws_dev;
+  size_t ws_bytes;
+} deft_job;
+
+int deft_sparsify(const deft_job* job, const float* g_dev, int64_t iteration, void* stream,
+                  void* norms_done_event, int32_t* my_count_out, int64_t* k_r_out);
 
 /*
  * Upper bound on the scratch bytes of a device call.

@@ -37,9 +37,20 @@ SIGNATURES = {
                               C.c_int64, _P, C.c_size_t, _P]),
     "topk_global": (C.c_int, [_P, C.c_int64, C.c_int64, _P, _P, _P, C.c_size_t, _P]),
     "deft_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int64, C.c_int32]),
+    "deft_sparsify": (C.c_int, [_P, _P, C.c_int64, _P, _P, _P, _P]),
 }
 
 _lib = None
+
+
+class DeftJob(C.Structure):
+    """struct deft_job of deft.h (the per-job arguments of deft_sparsify), field for field."""
+    _fields_ = [("N", C.c_int64), ("L", C.c_int32), ("n_workers", C.c_int32), ("rank", C.c_int32),
+                ("reserved", C.c_int32), ("d", C.c_double), ("offsets_host", _P),
+                ("offsets_dev", _P), ("sizes_host", _P), ("sumsq_pinned", _P), ("norms_host", _P),
+                ("k_host", _P), ("owner_bin_host", _P), ("my_layers_host", _P),
+                ("seg_off_host", _P), ("idx_out_dev", _P), ("val_out_dev", _P),
+                ("out_cap", C.c_int64), ("ws_dev", _P), ("ws_bytes", C.c_size_t)]
 
 
 class DeftError(RuntimeError):
@@ -192,3 +203,14 @@ def topk_global(g, K: int, idx_out, val_out, ws, stream=None) -> None:
                              idx_out.data_ptr(), val_out.data_ptr(),
                              ws.data_ptr(), ws.numel() * ws.element_size(),
                              _stream(stream)), "topk_global")
+
+
+def deft_sparsify(job: DeftJob, g, iteration: int, stream=None, norms_done_event: int = 0):
+    """The whole sparsifier call on g; returns (my_count, k_r).  Blocks until the norm pass has
+    delivered its sums; the selection is enqueued when it returns."""
+    cnt = C.c_int32(0)
+    kr = C.c_int64(0)
+    _check(lib().deft_sparsify(C.addressof(job), g.data_ptr(), int(iteration), _stream(stream),
+                               int(norms_done_event), C.addressof(cnt), C.addressof(kr)),
+           "deft_sparsify")
+    return int(cnt.value), int(kr.value)

@@ -25,6 +25,8 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
+#include <chrono>
 #include <cstdlib>
 #include <cstring>
 #include <vector>
@@ -1373,4 +1375,100 @@ extern "C" int topk_global(const float* g_dev, int64_t N, int64_t K, int32_t* id
   segs[0].hchunk_base = 0;
   return run_select(g_dev, segs, N, idx_out_dev, val_out_dev, ws_dev, ws_bytes,
                     static_cast<hipStream_t>(stream));
+}
+
+// ------------------------------------------------------------------------------------------
+// The whole sparsifier call (Sec. 4: norms -> Alg. 3 -> Alg. 4 -> Alg. 5) behind one entry.
+// ------------------------------------------------------------------------------------------
+namespace {
+// No sum of squares has this bit pattern: a NaN born from fp32 inputs keeps its low mantissa
+// bits clear, and the default NaN is 0x7ff8000000000000.
+constexpr uint64_t kSumUnset = ~uint64_t(0);
+
+// Read on every call so that a caller (or a test) can change it while the process runs.
+int64_t spin_limit_us() {
+  const char* e = std::getenv("DEFT_SPIN_US");
+  if (!e || !*e) return 20000;
+  const long long x = std::atoll(e);
+  return int64_t(x < 0 ? 0 : x);
+}
+
+// Waits until the norm pass has overwritten every armed entry.  Polls the pinned array for at
+// most spin_limit_us(), then blocks in hipStreamSynchronize.
+int await_sums(const double* sumsq_pinned, int32_t L, hipStream_t s) {
+  const volatile uint64_t* w = reinterpret_cast<const volatile uint64_t*>(sumsq_pinned);
+  int32_t cur = 0;
+  const int64_t limit = spin_limit_us();
+  if (limit > 0) {
+    const auto t0 = std::chrono::steady_clock::now();
+    uint32_t spins = 0;
+    for (;;) {
+      while (cur < L && w[cur] != kSumUnset) ++cur;
+      if (cur == L) break;
+      __builtin_ia32_pause();
+      if ((++spins & 255u) == 0 &&
+          std::chrono::duration_cast<std::chrono::microseconds>(std::chrono::steady_clock::now() - t0)
+                  .count() > limit)
+        break;
+    }
+  }
+  if (cur < L) {
+    HIP_TRY(hipStreamSynchronize(s));
+    while (cur < L && w[cur] != kSumUnset) ++cur;
+    if (cur < L) return DEFT_EHIP;
+  }
+  std::atomic_thread_fence(std::memory_order_acquire);
+  return DEFT_OK;
+}
+}  // namespace
+
+extern "C" int deft_sparsify(const deft_job* job, const float* g_dev, int64_t iteration,
+                             void* stream, void* norms_done_event, int32_t* my_count_out,
+                             int64_t* k_r_out) {
+  if (!job || !g_dev || !my_count_out || !k_r_out) return DEFT_EINVAL;
+  const deft_job& j = *job;
+  if (!j.offsets_host || !j.offsets_dev || !j.sizes_host || !j.sumsq_pinned || !j.norms_host ||
+      !j.k_host || !j.owner_bin_host || !j.my_layers_host || !j.seg_off_host || !j.ws_dev)
+    return DEFT_EINVAL;
+  if (j.n_workers < 1 || j.rank < 0 || j.rank >= j.n_workers || iteration < 0 ||
+      !(j.d > 0.0 && j.d <= 1.0) || j.out_cap < 0)
+    return DEFT_EINVAL;
+  int rc = deft_check_layout(j.offsets_host, j.L, j.N);
+  if (rc != DEFT_OK) return rc;
+  for (int32_t l = 0; l < j.L; ++l)
+    if (j.sizes_host[l] != j.offsets_host[l + 1] - j.offsets_host[l] || j.sizes_host[l] < 1)
+      return DEFT_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(g_dev) & 15u) || (reinterpret_cast<uintptr_t>(j.ws_dev) & 15u))
+    return DEFT_EINVAL;
+  if (j.ws_bytes < deft_workspace_bytes(DEFT_OP_SELECT, j.N, j.L) ||
+      j.ws_bytes < deft_workspace_bytes(DEFT_OP_NORMS, j.N, j.L))
+    return DEFT_EWS;
+  if (!j.idx_out_dev || !j.val_out_dev) return DEFT_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // Everything that can be refused without the data has been; from here on work is enqueued.
+
+  volatile uint64_t* arm = reinterpret_cast<volatile uint64_t*>(j.sumsq_pinned);
+  for (int32_t l = 0; l < j.L; ++l) arm[l] = kSumUnset;
+  std::atomic_thread_fence(std::memory_order_seq_cst);
+  rc = run_norms(g_dev, nullptr, 0.0f, nullptr, j.N, j.offsets_dev, j.L, j.sumsq_pinned, j.ws_dev,
+                 j.ws_bytes, stream);
+  if (rc != DEFT_OK) return rc;
+  if (norms_done_event) HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(norms_done_event), s));
+  rc = await_sums(j.sumsq_pinned, j.L, s);
+  if (rc != DEFT_OK) return rc;
+
+  rc = deft_norms_from_sumsq(j.sumsq_pinned, j.L, j.norms_host);
+  if (rc != DEFT_OK) return rc;
+  rc = deft_alloc_k(j.norms_host, j.sizes_host, j.L, j.N, j.d, j.k_host);
+  if (rc != DEFT_OK) return rc;
+  int32_t cnt = 0;
+  rc = deft_assign_layers(j.sizes_host, j.k_host, j.L, j.n_workers, iteration, j.rank,
+                          j.owner_bin_host, j.my_layers_host, &cnt);
+  if (rc != DEFT_OK) return rc;
+  rc = deft_select(g_dev, j.N, j.offsets_host, j.k_host, j.L, j.my_layers_host, cnt, j.idx_out_dev,
+                   j.val_out_dev, j.seg_off_host, j.out_cap, j.ws_dev, j.ws_bytes, stream);
+  if (rc != DEFT_OK) return rc;
+  *my_count_out = cnt;
+  *k_r_out = j.seg_off_host[cnt];
+  return DEFT_OK;
 }

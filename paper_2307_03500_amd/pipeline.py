@@ -80,6 +80,21 @@ class DeftSelector:
             "seg": self.seg_h.ctypes.data,
         }
         self._cap = cap
+        self._jobs = {}
+        self._cnt_c = B.C.c_int32(0)
+        self._kr_c = B.C.c_int64(0)
+        self._cnt_p, self._kr_p = B.C.addressof(self._cnt_c), B.C.addressof(self._kr_c)
+
+    def _job(self, rank: int) -> int:
+        """Address of this rank's deft_job (built once, kept alive by the selector)."""
+        j = self._jobs.get(rank)
+        if j is None:
+            p = self._p
+            j = B.DeftJob(self.N, self.L, self.n, int(rank), 0, self.d, p["off"], p["off_dev"],
+                          p["sizes"], p["sumsq"], p["norms"], p["k"], p["owner"], p["mine"],
+                          p["seg"], p["idx"], p["val"], self._cap, p["ws"], p["ws_bytes"])
+            self._jobs[rank] = j
+        return B.C.addressof(j)
 
     # -- steps (each is one or a few C-ABI calls on cached addresses) ----------------------
     def enqueue_norms(self, g: torch.Tensor, stream_handle: int) -> None:
@@ -139,6 +154,28 @@ class DeftSelector:
                          self.idx_out[:kr], self.val_out[:kr],
                          {"norm_ms": (t1 - t0) * 1e3, "plan_ms": (t2 - t1) * 1e3,
                           "select_ms": (t3 - t2) * 1e3})
+
+    def enqueue_sparsify(self, g: torch.Tensor, rank: int, iteration: int, stream_handle: int,
+                         norms_done_event: int = 0):
+        """deft_sparsify: the whole call in one library entry; returns (my_count, k_r) with the
+        selection enqueued (not yet complete) on the stream."""
+        rc = self._lib.deft_sparsify(self._job(rank), g.data_ptr(), iteration, stream_handle,
+                                     norms_done_event, self._cnt_p, self._kr_p)
+        if rc:
+            raise B.DeftError(rc, "deft_sparsify")
+        return self._cnt_c.value, self._kr_c.value
+
+    def sparsify(self, g: torch.Tensor, rank: int, iteration: int = 0) -> Selection:
+        """Same result as select(), through the single entry point."""
+        assert g.dtype == torch.float32 and g.numel() == self.N and g.device == self.device
+        st = torch.cuda.current_stream()
+        t0 = time.perf_counter()
+        cnt, kr = self.enqueue_sparsify(g, rank, iteration, st.cuda_stream)
+        st.synchronize()
+        t1 = time.perf_counter()
+        return Selection(self.norms_h.copy(), self.k_h.copy(), self.owner_h.copy(),
+                         self.mine_h[:cnt].copy(), self.seg_h[:cnt + 1].copy(),
+                         self.idx_out[:kr], self.val_out[:kr], {"step_ms": (t1 - t0) * 1e3})
 
     def select_with_plan(self, g: torch.Tensor, k: np.ndarray, my_layers: np.ndarray):
         """Alg. 5 alone, for a given (k, layer list)."""

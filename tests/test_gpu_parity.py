@@ -109,6 +109,47 @@ def test_deft_path_configs_all_ranks(deft, name):
     assert len(np.unique(allidx)) == len(allidx) == sum(o_k)
 
 
+@pytest.mark.parametrize("spin_us", ["20000", "0"])
+@pytest.mark.parametrize("name", ["toy_mlp", "resnet18", "lstm_lm"])
+def test_sparsify_single_entry_matches_oracle(deft, monkeypatch, name, spin_us):
+    """deft_sparsify (one call for Sec. 4's four steps) against the oracle, with the wait on
+    the pinned sums (spin) and with the stream-synchronise fallback (DEFT_SPIN_US=0); the
+    iteration argument rotates the bins (Alg. 4)."""
+    monkeypatch.setenv("DEFT_SPIN_US", spin_us)
+    gs = synth.make(name, seed=1)
+    sel = _selector(deft, gs.tensor_sizes, gs.n_workers, gs.d)
+    gd = torch.from_numpy(gs.g).to(DEV)
+    off, lay = sel.offsets.tolist(), sel.sizes.tolist()
+    o_norms = O.layer_norms(gs.g, off)
+    o_k = O.alloc_k(o_norms, lay, gs.N, gs.d)
+    for it, r in [(0, 0), (1, gs.n_workers - 1), (gs.n_workers + 2, 1), (3, 0)]:
+        res = sel.sparsify(gd, rank=r, iteration=it)
+        _check_norms(res.norms, o_norms)
+        assert res.k.tolist() == o_k
+        o_owner, o_part, _ = O.assign_layers(lay, o_k, gs.n_workers, it, r)
+        assert res.owner_bin.tolist() == o_owner and res.my_layers.tolist() == o_part
+        o_idx, o_val, o_seg = O.select(gs.g, off, o_k, o_part)
+        assert res.seg_off.tolist() == o_seg.tolist()
+        assert res.idx.tolist() == o_idx.tolist()
+        assert (_bits(res.val) == _bits(o_val)).all()
+        # and the step-wise calls give the same bits
+        idx1, val1 = res.idx.copy(), res.val.copy()
+        res2 = sel.select(gd, rank=r, iteration=it)
+        assert res2.idx.tolist() == idx1.tolist() and (_bits(res2.val) == _bits(val1)).all()
+
+
+def test_sparsify_reports_small_output_capacity_after_the_norm_pass(deft):
+    gs = synth.make("toy_mlp", seed=0)
+    sel = _selector(deft, gs.tensor_sizes, 1, 0.01, out_cap=5)  # one worker takes all K = 3009
+    sel._cap = 5
+    gd = torch.from_numpy(gs.g).to(DEV)
+    with pytest.raises(deft.DeftError) as ei:
+        sel.sparsify(gd, rank=0)
+    assert ei.value.status == deft.DEFT_ECAP
+    torch.cuda.synchronize()
+    _check_norms(sel.norms_h, O.layer_norms(gs.g, sel.offsets.tolist()))  # the plan is valid
+
+
 @pytest.mark.parametrize("name", ["toy_mlp", "resnet18", "lstm_lm", "ncf"])
 def test_topk_global_configs(deft, name):
     gs = synth.make(name, seed=0)

@@ -225,6 +225,41 @@ def test_device_calls_reject_bad_arguments_before_touching_the_gpu(deft):
     assert gz(N=2 ** 31) == B.DEFT_ERANGE
     assert gz(count=0, acc=0, idx=0, vals=0) == B.DEFT_OK
 
+    # deft_sparsify: every refusal comes before the first write to the caller's arrays
+    sizes = np.diff(off).astype(np.int64)
+    bufs = {"norms": np.zeros(2), "k": np.zeros(2, np.int64), "owner": np.zeros(2, np.int32),
+            "mine": np.zeros(2, np.int32), "seg": np.zeros(3, np.int64)}
+    cnt, kr = C.c_int32(-7), C.c_int64(-7)
+
+    def spars(g=0x1000, **over):
+        f = dict(N=16, L=2, n_workers=2, rank=0, reserved=0, d=0.25, offsets_host=off.ctypes.data,
+                 offsets_dev=0x5000, sizes_host=sizes.ctypes.data, sumsq_pinned=0x6000,
+                 norms_host=bufs["norms"].ctypes.data, k_host=bufs["k"].ctypes.data,
+                 owner_bin_host=bufs["owner"].ctypes.data, my_layers_host=bufs["mine"].ctypes.data,
+                 seg_off_host=bufs["seg"].ctypes.data, idx_out_dev=0x2000, val_out_dev=0x3000,
+                 out_cap=16, ws_dev=0x4000, ws_bytes=1 << 20)
+        f.update(over)
+        job = B.DeftJob(**f)
+        return lib.deft_sparsify(C.addressof(job), C.c_void_p(g), 0, None, None,
+                                 C.addressof(cnt), C.addressof(kr))
+
+    assert lib.deft_sparsify(None, C.c_void_p(0x1000), 0, None, None, C.addressof(cnt),
+                             C.addressof(kr)) == B.DEFT_EINVAL
+    assert spars(g=0) == B.DEFT_EINVAL
+    assert spars(g=0x1004) == B.DEFT_EINVAL
+    assert spars(rank=2) == B.DEFT_EINVAL
+    assert spars(n_workers=0) == B.DEFT_EINVAL
+    assert spars(d=0.0) == B.DEFT_EINVAL
+    assert spars(d=1.5) == B.DEFT_EINVAL
+    assert spars(N=17) == B.DEFT_EINVAL
+    wrong_sizes = np.array([8, 7], np.int64)
+    assert spars(sizes_host=wrong_sizes.ctypes.data) == B.DEFT_EINVAL
+    assert spars(sumsq_pinned=0) == B.DEFT_EINVAL
+    assert spars(idx_out_dev=0) == B.DEFT_EINVAL
+    assert spars(ws_dev=0x4004) == B.DEFT_EINVAL
+    assert spars(ws_bytes=64) == B.DEFT_EWS
+    assert cnt.value == -7 and kr.value == -7
+
     def topk(g=0x1000, N=16, K=4, idx=0x2000, val=0x3000, ws=0x4000, wsb=1 << 20):
         return lib.topk_global(C.c_void_p(g), N, K, C.c_void_p(idx), C.c_void_p(val),
                                C.c_void_p(ws), wsb, None)
