@@ -285,6 +285,16 @@ __global__ __launch_bounds__(kThreads) void seg_setup_kernel(SegBatch b, SegDesc
   }
 }
 
+// Exclusive prefix over the wavefront of a per-lane count in [0, 7], by three ballots.
+__device__ __forceinline__ uint32_t wave_excl_small(uint32_t cnt, uint32_t& total) {
+  const unsigned long long b0 = __ballot(cnt & 1u), b1 = __ballot(cnt & 2u), b2 = __ballot(cnt & 4u);
+  const int lane = threadIdx.x & 63;
+  const unsigned long long below = (1ull << lane) - 1ull;
+  total = (uint32_t)__popcll(b0) + 2u * (uint32_t)__popcll(b1) + 4u * (uint32_t)__popcll(b2);
+  return (uint32_t)__popcll(b0 & below) + 2u * (uint32_t)__popcll(b1 & below) +
+         4u * (uint32_t)__popcll(b2 & below);
+}
+
 // Segment that owns chunk c: largest j in [0, m-1] with seg[j].chunk_base <= c.
 __device__ __forceinline__ int seg_of_chunk(const SegDesc* __restrict__ seg, int m, uint32_t c) {
   int lo = 0, hi = m;
@@ -517,19 +527,20 @@ __global__ __launch_bounds__(kThreads) void hist0_kernel(const float* __restrict
   if ((threadIdx.x & 63) == 0 && top_bin > 0) atomicMax(&hmax[blockIdx.x], (uint32_t)top_bin);
 }
 
-// Pass 2 of 3 over the segment.  The top digit b0 of the threshold is known.  Keys with a
-// larger top digit are selected for sure and are only counted, per count/emit chunk; keys with
-// top digit b0 ("candidates", about as many as k) are histogrammed on their next digit AND
-// their low 20 bits are parked in a small per-chunk slot array, so that the remaining digit
-// levels and the per-chunk counts can be worked out from the slots without reading the
-// segment again.  A chunk with more candidates than slots is marked by its count; the later
-// kernels read such a chunk from the segment instead (heavy ties, dense selections).
-// A workgroup handles one histogram chunk = 4 count/emit chunks, one per wavefront.
+// Pass 2 of 3 over the segment.  The top digit b0 of the threshold is known.  Every key that can
+// still be selected -- top digit above b0 (selected for sure) or equal to b0 ("candidates"; the
+// two together are about as many as k) -- is parked with its index in a small per-chunk slot
+// array, in index order; candidates are also histogrammed on their next digit.  The remaining
+// digit level, the per-chunk counts AND the final ordered write are then worked out from the
+// slots, without reading the segment again.  A chunk with more such keys than slots is marked
+// by its count; the later kernels read that chunk from the segment instead (heavy ties, dense
+// selections).  A workgroup handles one histogram chunk = 4 count/emit chunks, one per
+// wavefront; a slot entry is {value bits, global index}.
 template <int ITERS, bool FUSED>
 __global__ __launch_bounds__(kThreads) void pass2_kernel(
     const float* __restrict__ g, const SegDesc* __restrict__ seg, SegState* __restrict__ st, int m,
-    uint32_t* __restrict__ hist, const uint32_t* __restrict__ hmax, uint32_t* __restrict__ n_sure,
-    uint32_t* __restrict__ cand_cnt, uint32_t* __restrict__ slots, uint32_t cap) {
+    uint32_t* __restrict__ hist, const uint32_t* __restrict__ hmax, uint32_t* __restrict__ live_cnt,
+    uint2* __restrict__ slots, uint32_t cap) {
   constexpr int HITERS = 4 * ITERS;
   constexpr int kBins = 1 << kBits1;
   __shared__ uint32_t lh[kBins];
@@ -544,44 +555,39 @@ __global__ __launch_bounds__(kThreads) void pass2_kernel(
   const uint32_t ec_local = local * 4 + wave;        // this wave's count/emit chunk
   const bool have_chunk = ec_local < n_chunks;
   if (hmax[blockIdx.x] < b0) {
-    // every key here lies below the threshold's bucket: nothing sure, no candidate, no read
-    if (lane == 0 && have_chunk) {
-      n_sure[d.chunk_base + ec_local] = 0;
-      cand_cnt[d.chunk_base + ec_local] = 0;
-    }
+    // every key here lies below the threshold's bucket: nothing to park, no read
+    if (lane == 0 && have_chunk) live_cnt[d.chunk_base + ec_local] = 0;
     return;
   }
   for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
   __syncthreads();
   Chunk<HITERS> ch;
   ch.load(g, d.start, (int64_t)d.start + d.size, local);
-  uint32_t* my_slots = slots + (size_t)(d.chunk_base + ec_local) * cap;
-  uint32_t sure = 0, filled = 0;
+  uint2* my_slots = slots + (size_t)(d.chunk_base + ec_local) * cap;
+  uint32_t filled = 0;
 #pragma unroll
   for (int i = 0; i < HITERS; ++i) {
+    uint32_t livem = 0;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      const uint32_t key = ch.key[i][c];
       const bool on = (ch.valid[i] >> c) & 1u;
-      const uint32_t top = key >> (kBits1 + kBits2);
-      sure += (on && top > b0) ? 1u : 0u;
-      const bool cand = on && top == b0;
-      const unsigned long long cb = __ballot(cand);
-      if (cb) {
-        if (cand) {
-          if (!s.done) atomicAdd(&lh[(key >> kBits2) & (kBins - 1)], 1u);
-          const uint32_t pos = filled + (uint32_t)__popcll(cb & ((1ull << lane) - 1ull));
-          if (pos < cap) my_slots[pos] = key & ((1u << (kBits1 + kBits2)) - 1u);
-        }
-        filled += (uint32_t)__popcll(cb);
+      livem |= (on && (ch.key[i][c] >> (kBits1 + kBits2)) >= b0) ? (1u << c) : 0u;
+    }
+    if (__ballot(livem != 0) == 0ull) continue;
+    uint32_t tot;
+    uint32_t pos = filled + wave_excl_small((uint32_t)__popc(livem), tot);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      if ((livem >> c) & 1u) {
+        const uint32_t key = ch.key[i][c];
+        if (!s.done && (key >> (kBits1 + kBits2)) == b0) atomicAdd(&lh[(key >> kBits2) & (kBins - 1)], 1u);
+        if (pos < cap) my_slots[pos] = make_uint2(ch.raw[i][c], (uint32_t)(ch.base + (int64_t)i * 256 + c));
+        ++pos;
       }
     }
+    filled += tot;
   }
-  sure = wave_sum_u32(sure);
-  if (lane == 0 && have_chunk) {
-    n_sure[d.chunk_base + ec_local] = sure;
-    cand_cnt[d.chunk_base + ec_local] = filled;
-  }
+  if (lane == 0 && have_chunk) live_cnt[d.chunk_base + ec_local] = filled;
   __syncthreads();
   if (s.done) return;
   uint32_t* gh = hist + (size_t)j * kHistStride + hist_offset(1);
@@ -596,8 +602,8 @@ __global__ __launch_bounds__(kThreads) void pass2_kernel(
 template <int ITERS, bool FUSED>
 __global__ __launch_bounds__(kThreads) void slot_hist2_kernel(
     const float* __restrict__ g, const SegDesc* __restrict__ seg, SegState* __restrict__ st, int m,
-    uint32_t* __restrict__ hist, const uint32_t* __restrict__ cand_cnt,
-    const uint32_t* __restrict__ slots, uint32_t cap) {
+    uint32_t* __restrict__ hist, const uint32_t* __restrict__ live_cnt,
+    const uint2* __restrict__ slots, uint32_t cap) {
   constexpr int kBins = 1 << kBits2;
   __shared__ uint32_t lh[kBins];
   __shared__ uint32_t fl[kWaves + 8];
@@ -606,14 +612,13 @@ __global__ __launch_bounds__(kThreads) void slot_hist2_kernel(
   const uint32_t local = blockIdx.x - d.chunk_base;
   const SegState s = state_after<2, FUSED>(st, m, j, hist, local == 0, fl);
   if (s.done) return;
-  const uint32_t n = cand_cnt[blockIdx.x];
+  const uint32_t n = live_cnt[blockIdx.x];
   if (n == 0) return;
   uint32_t* gh = hist + (size_t)j * kHistStride + hist_offset(2);
-  const uint32_t want = s.prefix & ((1u << kBits1) - 1u);  // second digit of the threshold
   if (n <= cap) {
     const bool on = threadIdx.x < n;
-    const uint32_t e = on ? slots[(size_t)blockIdx.x * cap + threadIdx.x] : 0u;
-    bool live = on && (e >> kBits2) == want;
+    const uint32_t e = on ? (slots[(size_t)blockIdx.x * cap + threadIdx.x].x & 0x7FFFFFFFu) : 0u;
+    bool live = on && (e >> kBits2) == s.prefix;  // the threshold's first two digits
     const uint32_t digit = e & (kBins - 1);
     // equal digits are common (rounded gradients): one atomic per distinct digit and wave
     unsigned long long act = __ballot(live);
@@ -658,14 +663,13 @@ __global__ __launch_bounds__(kThreads) void find_kernel(SegState* __restrict__ s
   if (threadIdx.x == 0) st[(size_t)(LEVEL + 1) * m + j] = s;
 }
 
-// Per count/emit chunk: how many keys exceed T and how many equal it -- from the sure count
-// and the slots of pass 2, or from the segment itself for a chunk that overflowed its slots.
-// n_sure and chunk_gt may be the same array.
+// Per count/emit chunk: how many keys exceed T and how many equal it -- from the slots of
+// pass 2, or from the segment itself for a chunk that overflowed its slots.
 template <int ITERS, bool FUSED>
 __global__ __launch_bounds__(kThreads) void slot_count_kernel(
     const float* __restrict__ g, const SegDesc* __restrict__ seg, SegState* __restrict__ st, int m,
-    const uint32_t* __restrict__ hist, const uint32_t* n_sure, const uint32_t* __restrict__ cand_cnt,
-    const uint32_t* __restrict__ slots, uint32_t cap, uint32_t* chunk_gt,
+    const uint32_t* __restrict__ hist, const uint32_t* __restrict__ live_cnt,
+    const uint2* __restrict__ slots, uint32_t cap, uint32_t* __restrict__ chunk_gt,
     uint32_t* __restrict__ chunk_eq) {
   __shared__ uint32_t red[2 * kWaves];
   __shared__ uint32_t fl[kWaves + 8];
@@ -673,17 +677,14 @@ __global__ __launch_bounds__(kThreads) void slot_count_kernel(
   const SegDesc d = seg[j];
   const uint32_t local = blockIdx.x - d.chunk_base;
   const uint32_t T = state_after<3, FUSED>(st, m, j, hist, local == 0, fl).T;
-  const uint32_t n = cand_cnt[blockIdx.x];
+  const uint32_t n = live_cnt[blockIdx.x];
   uint32_t gt = 0, eq = 0;
   if (n <= cap) {
-    // every candidate shares T's top digit, so comparing the low 20 bits compares the keys
-    const uint32_t t_low = T & ((1u << (kBits1 + kBits2)) - 1u);
     if (threadIdx.x < n) {
-      const uint32_t e = slots[(size_t)blockIdx.x * cap + threadIdx.x];
-      gt = e > t_low ? 1u : 0u;
-      eq = e == t_low ? 1u : 0u;
+      const uint32_t key = slots[(size_t)blockIdx.x * cap + threadIdx.x].x & 0x7FFFFFFFu;
+      gt = key > T ? 1u : 0u;
+      eq = key == T ? 1u : 0u;
     }
-    if (threadIdx.x == 0) gt += n_sure[blockIdx.x];
   } else {
     Chunk<ITERS> ch;
     ch.load(g, d.start, (int64_t)d.start + d.size, local);
@@ -717,8 +718,8 @@ __global__ __launch_bounds__(kThreads) void slot_count_kernel(
 template <int ITERS>
 __global__ __launch_bounds__(kThreads) void slot_hist2_wave_kernel(
     const float* __restrict__ g, const SegDesc* __restrict__ seg, const SegState* __restrict__ st,
-    int m, uint32_t chunks, uint32_t* __restrict__ hist, const uint32_t* __restrict__ cand_cnt,
-    const uint32_t* __restrict__ slots, uint32_t cap) {
+    int m, uint32_t chunks, uint32_t* __restrict__ hist, const uint32_t* __restrict__ live_cnt,
+    const uint2* __restrict__ slots, uint32_t cap) {
   constexpr int kBins = 1 << kBits2;
   __shared__ uint32_t lh[kBins];
   __shared__ uint32_t ovf[kWaves];
@@ -728,17 +729,16 @@ __global__ __launch_bounds__(kThreads) void slot_hist2_wave_kernel(
   if (c < chunks) {
     const int j = seg_of_chunk(seg, m, c);
     const SegState s = st[(size_t)2 * m + j];
-    const uint32_t n = cand_cnt[c];
+    const uint32_t n = live_cnt[c];
     if (!s.done && n > 0) {
       if (n > cap) {
         over = true;
       } else {
         uint32_t* gh = hist + (size_t)j * kHistStride + hist_offset(2);
-        const uint32_t want = s.prefix & ((1u << kBits1) - 1u);
         for (uint32_t r0 = 0; r0 < n; r0 += 64) {
           const bool on = r0 + lane < n;
-          const uint32_t e = on ? slots[(size_t)c * cap + r0 + lane] : 0u;
-          bool live = on && (e >> kBits2) == want;
+          const uint32_t e = on ? (slots[(size_t)c * cap + r0 + lane].x & 0x7FFFFFFFu) : 0u;
+          bool live = on && (e >> kBits2) == s.prefix;
           const uint32_t digit = e & (kBins - 1);
           unsigned long long act = __ballot(live);
           while (act) {
@@ -786,8 +786,8 @@ __global__ __launch_bounds__(kThreads) void slot_hist2_wave_kernel(
 template <int ITERS>
 __global__ __launch_bounds__(kThreads) void slot_count_wave_kernel(
     const float* __restrict__ g, const SegDesc* __restrict__ seg, const SegState* __restrict__ st,
-    int m, uint32_t chunks, const uint32_t* n_sure, const uint32_t* __restrict__ cand_cnt,
-    const uint32_t* __restrict__ slots, uint32_t cap, uint32_t* chunk_gt,
+    int m, uint32_t chunks, const uint32_t* __restrict__ live_cnt,
+    const uint2* __restrict__ slots, uint32_t cap, uint32_t* __restrict__ chunk_gt,
     uint32_t* __restrict__ chunk_eq) {
   __shared__ uint32_t red[2 * kWaves];
   __shared__ uint32_t ovf[kWaves];
@@ -797,23 +797,22 @@ __global__ __launch_bounds__(kThreads) void slot_count_wave_kernel(
   if (c < chunks) {
     const int j = seg_of_chunk(seg, m, c);
     const uint32_t T = st[(size_t)3 * m + j].T;
-    const uint32_t n = cand_cnt[c];
+    const uint32_t n = live_cnt[c];
     if (n > cap) {
       over = true;
     } else {
-      const uint32_t t_low = T & ((1u << (kBits1 + kBits2)) - 1u);
       uint32_t gt = 0, eq = 0;
       for (uint32_t r0 = 0; r0 < n; r0 += 64) {
         if (r0 + lane < n) {
-          const uint32_t e = slots[(size_t)c * cap + r0 + lane];
-          gt += e > t_low ? 1u : 0u;
-          eq += e == t_low ? 1u : 0u;
+          const uint32_t key = slots[(size_t)c * cap + r0 + lane].x & 0x7FFFFFFFu;
+          gt += key > T ? 1u : 0u;
+          eq += key == T ? 1u : 0u;
         }
       }
       gt = wave_sum_u32(gt);
       eq = wave_sum_u32(eq);
       if (lane == 0) {
-        chunk_gt[c] = gt + n_sure[c];
+        chunk_gt[c] = gt;
         chunk_eq[c] = eq;
       }
     }
@@ -918,19 +917,11 @@ __global__ __launch_bounds__(kThreads) void scan_tops_kernel(uint32_t* __restric
   }
 }
 
-// Exclusive prefix over the wavefront of a per-lane count in [0, 7], by three ballots.
-__device__ __forceinline__ uint32_t wave_excl_small(uint32_t cnt, uint32_t& total) {
-  const unsigned long long b0 = __ballot(cnt & 1u), b1 = __ballot(cnt & 2u), b2 = __ballot(cnt & 4u);
-  const int lane = threadIdx.x & 63;
-  const unsigned long long below = (1ull << lane) - 1ull;
-  total = (uint32_t)__popcll(b0) + 2u * (uint32_t)__popcll(b1) + 4u * (uint32_t)__popcll(b2);
-  return (uint32_t)__popcll(b0 & below) + 2u * (uint32_t)__popcll(b1 & below) +
-         4u * (uint32_t)__popcll(b2 & below);
-}
-
 // Ordered compaction of one chunk.  Ties are granted in index order until the quota r is used
 // up, so a chunk's first output slot is  out_off + (keys > T before it) + min(r, keys == T
-// before it)  within its segment.  SCAN_HERE: the workgroup sums the counts of the preceding
+// before it)  within its segment.  The chunk's selectable keys come from its slots (parked
+// by pass 2 in index order, one thread per entry); only a chunk that overflowed its slots is
+// read from the segment again.  SCAN_HERE: the workgroup sums the counts of the preceding
 // chunks of its segment itself -- cheaper than separate scan launches when every segment is
 // short; otherwise the prefixes come from scan_tiles_kernel / scan_tops_kernel.
 template <int ITERS, bool SCAN_HERE>
@@ -939,6 +930,7 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(
     int m, const uint32_t* __restrict__ chunk_gt, const uint32_t* __restrict__ chunk_eq,
     const uint32_t* __restrict__ pre_gt, const uint32_t* __restrict__ pre_eq,
     const uint32_t* __restrict__ tile_gt, const uint32_t* __restrict__ tile_eq,
+    const uint32_t* __restrict__ live_cnt, const uint2* __restrict__ slots, uint32_t cap,
     int32_t* __restrict__ idx_out, float* __restrict__ val_out) {
   __shared__ uint32_t wtot[2][kWaves];
   const int j = seg_of_chunk(seg, m, blockIdx.x);
@@ -973,9 +965,40 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(
   if (cgt == 0 && eb >= r) return;  // only ties here, and the quota was used up before them
   // 0: none of the chunk's ties is taken, 1: all are, 2: the quota ends inside this chunk
   const int mode = (eb >= r) ? 0 : ((r - eb >= ceq) ? 1 : 2);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t lim = d.out_off + d.k;  // a segment never writes past its own k slots
+  const uint32_t n_live = live_cnt[blockIdx.x];
+  if (n_live <= cap) {
+    const bool on = threadIdx.x < n_live;
+    const uint2 e = on ? slots[(size_t)blockIdx.x * cap + threadIdx.x] : make_uint2(0u, 0u);
+    const uint32_t key = e.x & 0x7FFFFFFFu;
+    const bool is_eq = on && key == T;
+    bool take = on && key > T;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    if (mode == 1) {
+      take = take || is_eq;
+    } else if (mode == 2) {
+      // the quota ends inside this chunk: rank its ties in index order
+      const unsigned long long eqb = __ballot(is_eq);
+      if (lane == 0) wtot[1][wave] = (uint32_t)__popcll(eqb);
+      __syncthreads();
+      uint32_t rank = eb + (uint32_t)__popcll(eqb & below);
+      for (int w = 0; w < wave; ++w) rank += wtot[1][w];
+      take = take || (is_eq && rank < r);
+    }
+    const unsigned long long tb = __ballot(take);
+    if (lane == 0) wtot[0][wave] = (uint32_t)__popcll(tb);
+    __syncthreads();
+    uint32_t pos = ob + (uint32_t)__popcll(tb & below);
+    for (int w = 0; w < wave; ++w) pos += wtot[0][w];
+    if (take && pos < lim) {
+      idx_out[pos] = (int32_t)e.y;
+      val_out[pos] = __uint_as_float(e.x);
+    }
+    return;
+  }
   Chunk<ITERS> ch;
   ch.load(g, d.start, (int64_t)d.start + d.size, blockIdx.x - d.chunk_base);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
   uint32_t sel[ITERS];  // 4-bit masks of selected components
   if (mode != 2) {
@@ -1034,7 +1057,6 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(
   uint32_t pos = ob;
   for (int w = 0; w < wave; ++w) pos += wtot[0][w];
   if (wtot[0][wave] == 0) return;
-  const uint32_t lim = d.out_off + d.k;  // a segment never writes past its own k slots
 #pragma unroll
   for (int i = 0; i < ITERS; ++i) {
     if (__ballot(sel[i] != 0) == 0ull) continue;
@@ -1085,13 +1107,12 @@ struct SelectLayout {
 
 constexpr uint32_t kMaxSlotCap = kThreads;  // one thread per slot entry in the slot kernels
 
-// Slots per count/emit chunk: about four times the candidates an average chunk should hold
-// (candidates are about as many as the selected entries), within [32, kMaxSlotCap].
-inline uint32_t slot_cap_for(uint64_t total_k, uint64_t share, uint32_t chunk_elems) {
-  const double expect = 4.0 * (double)chunk_elems * (double)total_k / (double)std::max<uint64_t>(share, 1);
-  uint32_t cap = 32;
-  while (cap < kMaxSlotCap && (double)cap < expect) cap *= 2;
-  return cap;
+// Slots per count/emit chunk.  Measured with caps sized to the average density (4x the
+// expected picks, 32..256): the conventional Top-k then overflowed in most chunks that hold
+// picks at all, because its picks sit in the few layers of large norm at many times the average
+// density.  The slot arrays are written sparsely, so the largest cap costs address space only.
+inline uint32_t slot_cap_for(uint64_t /*total_k*/, uint64_t /*share*/, uint32_t /*chunk_elems*/) {
+  return kMaxSlotCap;
 }
 
 SelectLayout select_layout(int64_t m, uint64_t chunks, uint32_t cap = kMaxSlotCap) {
@@ -1108,7 +1129,7 @@ SelectLayout select_layout(int64_t m, uint64_t chunks, uint32_t cap = kMaxSlotCa
   w.tgt = o;   o = align_up(o + sizeof(uint32_t) * (chunks / kScanTile + 1), 256);
   w.teq = o;   o = align_up(o + sizeof(uint32_t) * (chunks / kScanTile + 1), 256);
   w.ccnt = o;  o = align_up(o + sizeof(uint32_t) * chunks, 256);
-  w.slots = o; o = align_up(o + sizeof(uint32_t) * chunks * cap, 256);
+  w.slots = o; o = align_up(o + sizeof(uint2) * chunks * cap, 256);
   w.total = o;
   return w;
 }
@@ -1133,35 +1154,34 @@ template <int ITERS, bool FUSED>
 int launch_select(const float* g, const SegDesc* seg, SegState* st, int m, uint32_t chunks,
                   uint32_t hchunks, uint32_t* hist, uint32_t* cgt, uint32_t* ceq, uint32_t* obase,
                   uint32_t* ebase, uint32_t* tgt, uint32_t* teq, uint32_t* ccnt, uint32_t* hmax,
-                  uint32_t* slots,
+                  uint2* slots,
                   uint32_t cap, bool scan_in_emit,
                   int32_t* idx_out, float* val_out, hipStream_t s) {
   hist0_kernel<4 * ITERS, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, m, hist, hmax);
   if (!FUSED) find_kernel<0><<<m, kThreads, 0, s>>>(st, m, hist);
-  pass2_kernel<ITERS, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, st, m, hist, hmax, cgt, ccnt, slots,
-                                                          cap);
+  pass2_kernel<ITERS, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, st, m, hist, hmax, ccnt, slots, cap);
   if (!FUSED) find_kernel<1><<<m, kThreads, 0, s>>>(st, m, hist);
   if (FUSED) {
     slot_hist2_kernel<ITERS, true><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist, ccnt, slots, cap);
-    slot_count_kernel<ITERS, true><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist, cgt, ccnt, slots,
-                                                              cap, cgt, ceq);
+    slot_count_kernel<ITERS, true><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist, ccnt, slots, cap,
+                                                              cgt, ceq);
   } else {
     const uint32_t wblocks = (chunks + kWaves - 1) / kWaves;
     slot_hist2_wave_kernel<ITERS><<<wblocks, kThreads, 0, s>>>(g, seg, st, m, chunks, hist, ccnt,
                                                               slots, cap);
     find_kernel<2><<<m, kThreads, 0, s>>>(st, m, hist);
-    slot_count_wave_kernel<ITERS><<<wblocks, kThreads, 0, s>>>(g, seg, st, m, chunks, cgt, ccnt,
-                                                              slots, cap, cgt, ceq);
+    slot_count_wave_kernel<ITERS><<<wblocks, kThreads, 0, s>>>(g, seg, st, m, chunks, ccnt, slots,
+                                                              cap, cgt, ceq);
   }
   if (scan_in_emit) {
     emit_kernel<ITERS, true><<<chunks, kThreads, 0, s>>>(g, seg, st, m, cgt, ceq, obase, ebase, tgt,
-                                                         teq, idx_out, val_out);
+                                                         teq, ccnt, slots, cap, idx_out, val_out);
   } else {
     const uint32_t tiles = (chunks + kScanTile - 1) / kScanTile;
     scan_tiles_kernel<<<tiles, kThreads, 0, s>>>(cgt, ceq, chunks, obase, ebase, tgt, teq);
     scan_tops_kernel<<<1, kThreads, 0, s>>>(tgt, teq, tiles);
     emit_kernel<ITERS, false><<<chunks, kThreads, 0, s>>>(g, seg, st, m, cgt, ceq, obase, ebase, tgt,
-                                                          teq, idx_out, val_out);
+                                                          teq, ccnt, slots, cap, idx_out, val_out);
   }
   HIP_TRY(hipGetLastError());
   return DEFT_OK;
@@ -1220,7 +1240,7 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   uint32_t* te = reinterpret_cast<uint32_t*>(base + w.teq);
   uint32_t* cc = reinterpret_cast<uint32_t*>(base + w.ccnt);
   uint32_t* hm = reinterpret_cast<uint32_t*>(base + w.hmax);
-  uint32_t* sl = reinterpret_cast<uint32_t*>(base + w.slots);
+  uint2* sl = reinterpret_cast<uint2*>(base + w.slots);
   if (small)
     return launch_select<DEFT_SEL_ITERS_SMALL, true>(
         g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, tg, te, cc, hm, sl, cap,
