@@ -36,6 +36,11 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 constexpr int64_t kMaxN = (int64_t(1) << 31) - 1;
+constexpr uint32_t kMaxSlotCap = kThreads;  // one thread per slot entry in the slot kernels
+// Workgroups of the long-vector first pass: at least the resident set (256 CUs x 3), so every
+// slot is filled; latecomers find the counter exhausted and leave.
+constexpr uint32_t kStreamGrid = 1024;
+
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
@@ -324,7 +329,11 @@ struct Chunk {
   static constexpr int kElems = kThreads * 4 * ITERS;
   uint32_t key[ITERS][4];
   uint32_t raw[ITERS][4];
-  uint32_t valid[ITERS];  // 4-bit masks
+  uint32_t vbits[(ITERS + 7) / 8];  // a 4-bit mask of valid components per step, packed
+
+  __device__ __forceinline__ uint32_t vmask(int i) const {
+    return (vbits[i >> 3] >> ((i & 7) * 4)) & 0xFu;
+  }
   int64_t base;           // absolute index of this thread's vector in step 0
 
   __device__ __forceinline__ void load(const float* __restrict__ g, int64_t s, int64_t e,
@@ -337,28 +346,30 @@ struct Chunk {
       // interior chunk (uniform over the workgroup): all loads in flight together
       const v4u* __restrict__ p = reinterpret_cast<const v4u*>(g + base);
 #pragma unroll
+      for (int w = 0; w < (ITERS + 7) / 8; ++w) vbits[w] = 0xFFFFFFFFu;
+#pragma unroll
       for (int i = 0; i < ITERS; ++i) {
         const v4u v = __builtin_nontemporal_load(&p[i * 64]);  // streamed: keep it out of L2's way
         raw[i][0] = v.x; raw[i][1] = v.y; raw[i][2] = v.z; raw[i][3] = v.w;
-        valid[i] = 0xF;
       }
     } else {
+#pragma unroll
+      for (int w = 0; w < (ITERS + 7) / 8; ++w) vbits[w] = 0u;
 #pragma unroll
       for (int i = 0; i < ITERS; ++i) {
         const int64_t p = base + (int64_t)i * 256;
         if (p >= s && p + 4 <= e) {
           const uint4 v = *reinterpret_cast<const uint4*>(g + p);
           raw[i][0] = v.x; raw[i][1] = v.y; raw[i][2] = v.z; raw[i][3] = v.w;
-          valid[i] = 0xF;
+          vbits[i >> 3] |= 0xFu << ((i & 7) * 4);
         } else {
-          valid[i] = 0;
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             const int64_t q = p + c;
             raw[i][c] = 0;
             if (q >= s && q < e) {
               raw[i][c] = __float_as_uint(g[q]);
-              valid[i] |= 1u << c;
+              vbits[i >> 3] |= 1u << ((i & 7) * 4 + c);
             }
           }
         }
@@ -501,7 +512,7 @@ __global__ __launch_bounds__(kThreads) void hist0_kernel(const float* __restrict
     const uint32_t d0 = ch.key[i][0] >> kShift;
 #ifndef DEFT_HIST0_PLAIN
     const uint32_t dl = (uint32_t)__builtin_amdgcn_readfirstlane((int)d0);
-    const bool same = ch.valid[i] == 0xF && d0 == dl && (ch.key[i][1] >> kShift) == dl &&
+    const bool same = ch.vmask(i) == 0xF && d0 == dl && (ch.key[i][1] >> kShift) == dl &&
                       (ch.key[i][2] >> kShift) == dl && (ch.key[i][3] >> kShift) == dl;
     if (__ballot(!same) == 0ull) {
       if ((threadIdx.x & 63) == 0) atomicAdd(&lh[dl], 256u);
@@ -510,7 +521,7 @@ __global__ __launch_bounds__(kThreads) void hist0_kernel(const float* __restrict
 #endif
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      if ((ch.valid[i] >> c) & 1u) atomicAdd(&lh[ch.key[i][c] >> kShift], 1u);
+      if ((ch.vmask(i) >> c) & 1u) atomicAdd(&lh[ch.key[i][c] >> kShift], 1u);
     }
   }
   __syncthreads();
@@ -525,6 +536,78 @@ __global__ __launch_bounds__(kThreads) void hist0_kernel(const float* __restrict
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) top_bin = max(top_bin, __shfl_down(top_bin, o, 64));
   if ((threadIdx.x & 63) == 0 && top_bin > 0) atomicMax(&hmax[blockIdx.x], (uint32_t)top_bin);
+}
+
+// Pass 1 for long vectors.  Merging a workgroup's histogram into the segment's costs one
+// device-scope atomic per occupied bin; with one chunk per workgroup that merge took a quarter
+// of the pass on a 1.4 GB vector (281 us; 211 us with the merge left out, 238 / 219 us when
+// only every 4th / 20th workgroup merged).  Here a resident set of workgroups draws chunks from
+// a counter (the next draw is issued before the current chunk is processed) and keeps
+// accumulating in LDS; a workgroup merges when its next chunk belongs to another segment and
+// when the chunks run out.  The counter only grows, so every workgroup leaves its loop.  The
+// largest top digit of each chunk comes from the keys (the LDS histogram now spans chunks).
+template <int HITERS>
+__global__ __launch_bounds__(kThreads) void hist0_stream_kernel(
+    const float* __restrict__ g, const SegDesc* __restrict__ seg, int m, uint32_t hchunks,
+    uint32_t* __restrict__ hist, uint32_t* __restrict__ hmax, uint32_t* __restrict__ next_chunk) {
+  constexpr int kBins = 1 << kBits0;
+  constexpr int kShift = kBits1 + kBits2;
+  __shared__ uint32_t lh[kBins];
+  __shared__ uint32_t draw[2];
+  for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
+  if (threadIdx.x == 0) draw[0] = atomicAdd(next_chunk, 1u);
+  __syncthreads();
+  uint32_t c = draw[0];
+  int cur = -1, turn = 0;
+  while (c < hchunks) {
+    if (threadIdx.x == 0) draw[turn ^ 1] = atomicAdd(next_chunk, 1u);
+    const int j = seg_of_hchunk(seg, m, c);
+    if (j != cur) {
+      if (cur >= 0) {
+        uint32_t* gh = hist + (size_t)cur * kHistStride + hist_offset(0);
+        for (int b = threadIdx.x; b < kBins; b += kThreads) {
+          const uint32_t v = lh[b];
+          if (v) { atomicAdd(&gh[b], v); lh[b] = 0; }
+        }
+        __syncthreads();
+      }
+      cur = j;
+    }
+    const SegDesc d = seg[j];
+    Chunk<HITERS> ch;
+    ch.load(g, d.start, (int64_t)d.start + d.size, c - d.hchunk_base);
+    uint32_t mx = 0;
+#pragma unroll
+    for (int i = 0; i < HITERS; ++i) {
+      mx = max(mx, max(max(ch.key[i][0], ch.key[i][1]), max(ch.key[i][2], ch.key[i][3])));
+      // a wavefront whose 256 keys of a step share one digit adds once (see hist0_kernel)
+      const uint32_t d0 = ch.key[i][0] >> kShift;
+      const uint32_t dl = (uint32_t)__builtin_amdgcn_readfirstlane((int)d0);
+      const bool same = ch.vmask(i) == 0xF && d0 == dl && (ch.key[i][1] >> kShift) == dl &&
+                        (ch.key[i][2] >> kShift) == dl && (ch.key[i][3] >> kShift) == dl;
+      if (__ballot(!same) == 0ull) {
+        if ((threadIdx.x & 63) == 0) atomicAdd(&lh[dl], 256u);
+        continue;
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if ((ch.vmask(i) >> q) & 1u) atomicAdd(&lh[ch.key[i][q] >> kShift], 1u);
+      }
+    }
+    int top_bin = (int)(mx >> kShift);  // masked elements carry key 0
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) top_bin = max(top_bin, __shfl_down(top_bin, o, 64));
+    if ((threadIdx.x & 63) == 0 && top_bin > 0) atomicMax(&hmax[c], (uint32_t)top_bin);
+    __syncthreads();  // the chunk is in the histogram and draw[turn ^ 1] is visible
+    turn ^= 1;
+    c = draw[turn];
+  }
+  if (cur < 0) return;
+  uint32_t* gh = hist + (size_t)cur * kHistStride + hist_offset(0);
+  for (int b = threadIdx.x; b < kBins; b += kThreads) {
+    const uint32_t v = lh[b];
+    if (v) atomicAdd(&gh[b], v);
+  }
 }
 
 // Pass 2 of 3 over the segment.  The top digit b0 of the threshold is known.  Every key that can
@@ -570,7 +653,7 @@ __global__ __launch_bounds__(kThreads) void pass2_kernel(
     uint32_t livem = 0;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      const bool on = (ch.valid[i] >> c) & 1u;
+      const bool on = (ch.vmask(i) >> c) & 1u;
       livem |= (on && (ch.key[i][c] >> (kBits1 + kBits2)) >= b0) ? (1u << c) : 0u;
     }
     if (__ballot(livem != 0) == 0ull) continue;
@@ -641,7 +724,7 @@ __global__ __launch_bounds__(kThreads) void slot_hist2_kernel(
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       const uint32_t key = ch.key[i][c];
-      if (((ch.valid[i] >> c) & 1u) && (key >> kBits2) == s.prefix) atomicAdd(&lh[key & (kBins - 1)], 1u);
+      if (((ch.vmask(i) >> c) & 1u) && (key >> kBits2) == s.prefix) atomicAdd(&lh[key & (kBins - 1)], 1u);
     }
   }
   __syncthreads();
@@ -692,7 +775,7 @@ __global__ __launch_bounds__(kThreads) void slot_count_kernel(
     for (int i = 0; i < ITERS; ++i) {
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const bool on = (ch.valid[i] >> c) & 1u;
+        const bool on = (ch.vmask(i) >> c) & 1u;
         gt += (on && ch.key[i][c] > T) ? 1u : 0u;
         eq += (on && ch.key[i][c] == T) ? 1u : 0u;
       }
@@ -771,7 +854,7 @@ __global__ __launch_bounds__(kThreads) void slot_hist2_wave_kernel(
 #pragma unroll
       for (int cc = 0; cc < 4; ++cc) {
         const uint32_t key = ch.key[i][cc];
-        if (((ch.valid[i] >> cc) & 1u) && (key >> kBits2) == prefix) atomicAdd(&lh[key & (kBins - 1)], 1u);
+        if (((ch.vmask(i) >> cc) & 1u) && (key >> kBits2) == prefix) atomicAdd(&lh[key & (kBins - 1)], 1u);
       }
     }
     __syncthreads();
@@ -832,7 +915,7 @@ __global__ __launch_bounds__(kThreads) void slot_count_wave_kernel(
     for (int i = 0; i < ITERS; ++i) {
 #pragma unroll
       for (int cc = 0; cc < 4; ++cc) {
-        const bool on = (ch.valid[i] >> cc) & 1u;
+        const bool on = (ch.vmask(i) >> cc) & 1u;
         gt += (on && ch.key[i][cc] > T) ? 1u : 0u;
         eq += (on && ch.key[i][cc] == T) ? 1u : 0u;
       }
@@ -1007,7 +1090,7 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(
       sel[i] = 0;
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const bool on = (ch.valid[i] >> c) & 1u;
+        const bool on = (ch.vmask(i) >> c) & 1u;
         const bool s = mode == 1 ? ch.key[i][c] >= T : ch.key[i][c] > T;
         sel[i] |= (on && s) ? (1u << c) : 0u;
       }
@@ -1021,7 +1104,7 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(
       eqm[i] = 0;
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const bool on = (ch.valid[i] >> c) & 1u;
+        const bool on = (ch.vmask(i) >> c) & 1u;
         eqm[i] |= (on && ch.key[i][c] == T) ? (1u << c) : 0u;
       }
       wave_eq += (uint32_t)__popc(eqm[i]);
@@ -1038,7 +1121,7 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(
       sel[i] = 0;
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const bool on = (ch.valid[i] >> c) & 1u;
+        const bool on = (ch.vmask(i) >> c) & 1u;
         const bool is_eq = (eqm[i] >> c) & 1u;
         bool s = on && ch.key[i][c] > T;
         if (is_eq) { s = mine < r; ++mine; }
@@ -1105,8 +1188,6 @@ struct SelectLayout {
   size_t seg, st, hist, cgt, ceq, obase, ebase, tgt, teq, ccnt, hmax, slots, total;
 };
 
-constexpr uint32_t kMaxSlotCap = kThreads;  // one thread per slot entry in the slot kernels
-
 // Slots per count/emit chunk.  Measured with caps sized to the average density (4x the
 // expected picks, 32..256): the conventional Top-k then overflowed in most chunks that hold
 // picks at all, because its picks sit in the few layers of large norm at many times the average
@@ -1121,7 +1202,7 @@ SelectLayout select_layout(int64_t m, uint64_t chunks, uint32_t cap = kMaxSlotCa
   w.seg = o;   o = align_up(o + sizeof(SegDesc) * (size_t)(m + 1), 256);
   w.st = o;    o = align_up(o + sizeof(SegState) * 4 * (size_t)m, 256);  // state after 0..3 levels
   w.hist = o;  o = o + sizeof(uint32_t) * kHistStride * (size_t)m;  // hmax follows: zeroed together
-  w.hmax = o;  o = align_up(o + sizeof(uint32_t) * (chunks / 4 + 2 * (size_t)m + 1), 256);
+  w.hmax = o;  o = align_up(o + sizeof(uint32_t) * (chunks / 4 + 2 * (size_t)m + 2), 256);
   w.cgt = o;   o = align_up(o + sizeof(uint32_t) * chunks, 256);
   w.ceq = o;   o = align_up(o + sizeof(uint32_t) * chunks, 256);
   w.obase = o; o = align_up(o + sizeof(uint32_t) * chunks, 256);
@@ -1157,8 +1238,14 @@ int launch_select(const float* g, const SegDesc* seg, SegState* st, int m, uint3
                   uint2* slots,
                   uint32_t cap, bool scan_in_emit,
                   int32_t* idx_out, float* val_out, hipStream_t s) {
-  hist0_kernel<4 * ITERS, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, m, hist, hmax);
-  if (!FUSED) find_kernel<0><<<m, kThreads, 0, s>>>(st, m, hist);
+  if (FUSED) {
+    hist0_kernel<4 * ITERS, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, m, hist, hmax);
+  } else {
+    // hmax[hchunks] is the chunk counter (zeroed with the histograms by seg_setup_kernel)
+    hist0_stream_kernel<4 * ITERS><<<std::min<uint32_t>(hchunks, kStreamGrid), kThreads, 0, s>>>(
+        g, seg, m, hchunks, hist, hmax, hmax + hchunks);
+    find_kernel<0><<<m, kThreads, 0, s>>>(st, m, hist);
+  }
   pass2_kernel<ITERS, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, st, m, hist, hmax, ccnt, slots, cap);
   if (!FUSED) find_kernel<1><<<m, kThreads, 0, s>>>(st, m, hist);
   if (FUSED) {
@@ -1219,7 +1306,8 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   SegDesc* seg = reinterpret_cast<SegDesc*>(base + w.seg);
   SegState* st = reinterpret_cast<SegState*>(base + w.st);
   uint32_t* hist = reinterpret_cast<uint32_t*>(base + w.hist);
-  const size_t nzero = (size_t)kHistStride * m + hchunks;  // histograms and the per-chunk maxima
+  // histograms, the per-chunk maxima and the chunk counter of the long-vector first pass
+  const size_t nzero = (size_t)kHistStride * m + hchunks + 1;
   const unsigned setup_blocks = (unsigned)std::min<size_t>((nzero + 4 * kThreads - 1) / (4 * kThreads), 256);
   for (int first = 0; first < m; first += kSegBatch) {
     SegBatch b;
