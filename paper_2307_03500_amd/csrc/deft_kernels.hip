@@ -803,66 +803,103 @@ __global__ __launch_bounds__(kThreads) void slot_hist2_wave_kernel(
     const float* __restrict__ g, const SegDesc* __restrict__ seg, const SegState* __restrict__ st,
     int m, uint32_t chunks, uint32_t* __restrict__ hist, const uint32_t* __restrict__ live_cnt,
     const uint2* __restrict__ slots, uint32_t cap) {
+  // The workgroups stride over groups of kWaves consecutive chunks and collect the digits in an
+  // LDS histogram that is merged into the segment's when the segment changes and at the end:
+  // rounded gradients put every candidate into the same few bins, and one device-scope atomic
+  // per wavefront and chunk on those few addresses took 42 us on a 1.4 GB vector.  A group that
+  // straddles two segments (rare) adds to the segments' histograms directly.
   constexpr int kBins = 1 << kBits2;
-  __shared__ uint32_t lh[kBins];
+  __shared__ uint32_t acc[kBins];  // digits of segment `cur`, not yet merged
+  __shared__ uint32_t lh[kBins];   // scratch of the overflow path
   __shared__ uint32_t ovf[kWaves];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const uint32_t c = blockIdx.x * kWaves + wave;
-  bool over = false;
-  if (c < chunks) {
-    const int j = seg_of_chunk(seg, m, c);
-    const SegState s = st[(size_t)2 * m + j];
-    const uint32_t n = live_cnt[c];
-    if (!s.done && n > 0) {
-      if (n > cap) {
-        over = true;
-      } else {
-        uint32_t* gh = hist + (size_t)j * kHistStride + hist_offset(2);
-        for (uint32_t r0 = 0; r0 < n; r0 += 64) {
-          const bool on = r0 + lane < n;
-          const uint32_t e = on ? (slots[(size_t)c * cap + r0 + lane].x & 0x7FFFFFFFu) : 0u;
-          bool live = on && (e >> kBits2) == s.prefix;
-          const uint32_t digit = e & (kBins - 1);
-          unsigned long long act = __ballot(live);
-          while (act) {
-            const int leader = __ffsll((long long)act) - 1;
-            const uint32_t dl = (uint32_t)__builtin_amdgcn_readlane((int)digit, leader);
-            const unsigned long long same = __ballot(live && digit == dl);
-            if (lane == leader) atomicAdd(&gh[dl], (uint32_t)__popcll(same));
-            if (live && digit == dl) live = false;
-            act &= ~same;
+  for (int b = threadIdx.x; b < kBins; b += kThreads) acc[b] = 0;
+  __syncthreads();
+  int cur = -1;
+  const uint32_t groups = (chunks + kWaves - 1) / kWaves;
+  for (uint32_t grp = blockIdx.x; grp < groups; grp += gridDim.x) {
+    const uint32_t c0 = grp * kWaves;
+    const int j0 = seg_of_chunk(seg, m, c0);
+    const bool one_seg = seg_of_chunk(seg, m, min(c0 + kWaves - 1, chunks - 1)) == j0;
+    if (one_seg && j0 != cur) {
+      if (cur >= 0) {
+        __syncthreads();
+        uint32_t* gh = hist + (size_t)cur * kHistStride + hist_offset(2);
+        for (int b = threadIdx.x; b < kBins; b += kThreads) {
+          const uint32_t v = acc[b];
+          if (v) { atomicAdd(&gh[b], v); acc[b] = 0; }
+        }
+        __syncthreads();
+      }
+      cur = j0;
+    }
+    const uint32_t c = c0 + wave;
+    bool over = false;
+    if (c < chunks) {
+      const int j = one_seg ? j0 : seg_of_chunk(seg, m, c);
+      const SegState s = st[(size_t)2 * m + j];
+      const uint32_t n = live_cnt[c];
+      if (!s.done && n > 0) {
+        if (n > cap) {
+          over = true;
+        } else {
+          uint32_t* dst = one_seg ? acc : hist + (size_t)j * kHistStride + hist_offset(2);
+          for (uint32_t r0 = 0; r0 < n; r0 += 64) {
+            const bool on = r0 + lane < n;
+            const uint32_t e = on ? (slots[(size_t)c * cap + r0 + lane].x & 0x7FFFFFFFu) : 0u;
+            bool live = on && (e >> kBits2) == s.prefix;
+            const uint32_t digit = e & (kBins - 1);
+            // equal digits are common: one atomic per distinct digit and wavefront
+            unsigned long long act = __ballot(live);
+            while (act) {
+              const int leader = __ffsll((long long)act) - 1;
+              const uint32_t dl = (uint32_t)__builtin_amdgcn_readlane((int)digit, leader);
+              const unsigned long long same = __ballot(live && digit == dl);
+              if (lane == leader) atomicAdd(&dst[dl], (uint32_t)__popcll(same));
+              if (live && digit == dl) live = false;
+              act &= ~same;
+            }
           }
         }
       }
     }
-  }
-  if (lane == 0) ovf[wave] = over ? 1u : 0u;
-  __syncthreads();
-  for (int q = 0; q < kWaves; ++q) {
-    if (!ovf[q]) continue;
-    const uint32_t cq = blockIdx.x * kWaves + q;
-    const int j = seg_of_chunk(seg, m, cq);
-    const SegDesc d = seg[j];
-    const uint32_t prefix = st[(size_t)2 * m + j].prefix;
+    if (lane == 0) ovf[wave] = over ? 1u : 0u;
     __syncthreads();
-    for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
-    __syncthreads();
-    Chunk<ITERS> ch;
-    ch.load(g, d.start, (int64_t)d.start + d.size, cq - d.chunk_base);
+    // chunks that overflowed their slots: the whole workgroup reads them from the segment
+    for (int q = 0; q < kWaves; ++q) {
+      if (!ovf[q]) continue;
+      const uint32_t cq = c0 + q;
+      const int j = seg_of_chunk(seg, m, cq);
+      const SegDesc d = seg[j];
+      const uint32_t prefix = st[(size_t)2 * m + j].prefix;
+      __syncthreads();
+      for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
+      __syncthreads();
+      Chunk<ITERS> ch;
+      ch.load(g, d.start, (int64_t)d.start + d.size, cq - d.chunk_base);
 #pragma unroll
-    for (int i = 0; i < ITERS; ++i) {
+      for (int i = 0; i < ITERS; ++i) {
 #pragma unroll
-      for (int cc = 0; cc < 4; ++cc) {
-        const uint32_t key = ch.key[i][cc];
-        if (((ch.vmask(i) >> cc) & 1u) && (key >> kBits2) == prefix) atomicAdd(&lh[key & (kBins - 1)], 1u);
+        for (int cc = 0; cc < 4; ++cc) {
+          const uint32_t key = ch.key[i][cc];
+          if (((ch.vmask(i) >> cc) & 1u) && (key >> kBits2) == prefix) atomicAdd(&lh[key & (kBins - 1)], 1u);
+        }
+      }
+      __syncthreads();
+      uint32_t* gh = hist + (size_t)j * kHistStride + hist_offset(2);
+      for (int b = threadIdx.x; b < kBins; b += kThreads) {
+        const uint32_t v = lh[b];
+        if (v) atomicAdd(&gh[b], v);
       }
     }
-    __syncthreads();
-    uint32_t* gh = hist + (size_t)j * kHistStride + hist_offset(2);
-    for (int b = threadIdx.x; b < kBins; b += kThreads) {
-      const uint32_t v = lh[b];
-      if (v) atomicAdd(&gh[b], v);
-    }
+    __syncthreads();  // ovf[] may be rewritten
+  }
+  if (cur < 0) return;
+  __syncthreads();
+  uint32_t* gh = hist + (size_t)cur * kHistStride + hist_offset(2);
+  for (int b = threadIdx.x; b < kBins; b += kThreads) {
+    const uint32_t v = acc[b];
+    if (v) atomicAdd(&gh[b], v);
   }
 }
 
@@ -1254,8 +1291,8 @@ int launch_select(const float* g, const SegDesc* seg, SegState* st, int m, uint3
                                                               cgt, ceq);
   } else {
     const uint32_t wblocks = (chunks + kWaves - 1) / kWaves;
-    slot_hist2_wave_kernel<ITERS><<<wblocks, kThreads, 0, s>>>(g, seg, st, m, chunks, hist, ccnt,
-                                                              slots, cap);
+    slot_hist2_wave_kernel<ITERS><<<std::min<uint32_t>(wblocks, kStreamGrid), kThreads, 0, s>>>(
+        g, seg, st, m, chunks, hist, ccnt, slots, cap);
     find_kernel<2><<<m, kThreads, 0, s>>>(st, m, hist);
     slot_count_wave_kernel<ITERS><<<wblocks, kThreads, 0, s>>>(g, seg, st, m, chunks, ccnt, slots,
                                                               cap, cgt, ceq);
