@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstring>
 #include <numeric>
 #include <vector>
 
@@ -82,6 +83,23 @@ extern "C" int deft_check_layout(const int64_t* offsets, int32_t L, int64_t N) {
   return DEFT_OK;
 }
 
+namespace {
+// Sorting by (value descending, position ascending) for non-negative finite doubles: their bit
+// patterns order like the values, so one integer compare of (~bits, position) does both.
+// Adding +0.0 turns a -0.0 into +0.0, which compares equal and must sort as equal.
+typedef unsigned __int128 SortKey;
+void sort_descending(const double* v, int32_t L, std::vector<SortKey>& out) {
+  out.resize(L);
+  for (int32_t l = 0; l < L; ++l) {
+    const double x = v[l] + 0.0;
+    uint64_t bits;
+    std::memcpy(&bits, &x, sizeof bits);
+    out[l] = ((SortKey)(~bits) << 32) | (uint32_t)l;
+  }
+  std::sort(out.begin(), out.end());
+}
+}  // namespace
+
 extern "C" int deft_norms_from_sumsq(const double* sumsq, int32_t L, double* norms) {
   if (!sumsq || !norms || L < 1) return DEFT_EINVAL;
   for (int32_t l = 0; l < L; ++l)
@@ -103,14 +121,13 @@ extern "C" int deft_alloc_k(const double* norms, const int64_t* sizes, int32_t L
     if (!(norms[l] >= 0.0) || !std::isfinite(norms[l])) return DEFT_EINVAL;
   }
   // priority order: norm descending, position ascending among equal norms
-  std::vector<std::pair<double, int32_t>> keyed(L);
-  for (int32_t l = 0; l < L; ++l) keyed[l] = {norms[l], l};
-  std::sort(keyed.begin(), keyed.end(), [](const auto& a, const auto& b) {
-    return a.first > b.first || (a.first == b.first && a.second < b.second);
-  });
-  std::vector<int32_t> order(L);
-  for (int32_t j = 0; j < L; ++j) order[j] = keyed[j].second;
-  std::vector<double> norm_remain(L);
+  thread_local std::vector<SortKey> keyed;
+  thread_local std::vector<int32_t> order;
+  thread_local std::vector<double> norm_remain;
+  sort_descending(norms, L, keyed);
+  order.resize(L);
+  for (int32_t j = 0; j < L; ++j) order[j] = (int32_t)(uint32_t)keyed[j];
+  norm_remain.resize(L);
   double acc = 0.0;
   for (int32_t j = L - 1; j >= 0; --j) {
     acc = norms[order[j]] + acc;
@@ -154,25 +171,26 @@ extern "C" int deft_assign_layers(const int64_t* sizes, const int64_t* k, int32_
   const int32_t cycle = (int32_t)(iteration % n_workers);
   const int32_t curr_part = (cycle + rank) % n_workers;
   // layers in (cost descending, position ascending) order
-  std::vector<std::pair<double, int32_t>> item(L);
+  thread_local std::vector<double> cost;
+  thread_local std::vector<SortKey> item;
+  thread_local std::vector<std::pair<double, int32_t>> heap;
+  cost.resize(L);
   for (int32_t l = 0; l < L; ++l)
-    item[l] = {k[l] == 1 ? 0.0 : (double)sizes[l] * std::log((double)k[l]), l};
-  std::sort(item.begin(), item.end(), [](const auto& a, const auto& b) {
-    return a.first > b.first || (a.first == b.first && a.second < b.second);
-  });
+    cost[l] = k[l] == 1 ? 0.0 : (double)sizes[l] * std::log((double)k[l]);
+  sort_descending(cost.data(), L, item);
   // bins as a binary min-heap on (load, id): its top is the first bin of minimal load
-  std::vector<std::pair<double, int32_t>> heap(n_workers);
+  heap.resize(n_workers);
   for (int32_t b = 0; b < n_workers; ++b) heap[b] = {0.0, b};  // already a valid heap
   const auto lighter = [](const std::pair<double, int32_t>& a, const std::pair<double, int32_t>& b) {
     return a.first < b.first || (a.first == b.first && a.second < b.second);
   };
   int32_t cnt = 0;
   for (int32_t j = 0; j < L; ++j) {
-    const int32_t idx_max = item[j].second;
+    const int32_t idx_max = (int32_t)(uint32_t)item[j];
     const int32_t bin_min = heap[0].second;
     owner_bin[idx_max] = bin_min;
     if (bin_min == curr_part) my_layers[cnt++] = idx_max;
-    heap[0].first = heap[0].first + item[j].first;
+    heap[0].first = heap[0].first + cost[idx_max];
     // sift the grown bin down
     int32_t i = 0;
     for (;;) {
