@@ -264,18 +264,10 @@ static_assert(sizeof(SegBatch) <= 4000, "kernel argument block too large");
 
 constexpr int kBits0 = 11, kBits1 = 10, kBits2 = 10;
 
-// Writes one batch of segment descriptors (passed as kernel arguments) and their initial
-// state; the first batch also clears the histograms.
-__global__ __launch_bounds__(kThreads) void seg_setup_kernel(SegBatch b, SegDesc* __restrict__ seg,
-                                                             SegState* __restrict__ st,
-                                                             uint32_t* __restrict__ zero_from,
-                                                             size_t zero_count) {
-  if (b.first == 0) {
-    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < zero_count;
-         i += (size_t)gridDim.x * kThreads)
-      zero_from[i] = 0u;
-  }
-  if (blockIdx.x != 0) return;
+// Run by one workgroup: stores a batch of segment descriptors (passed as kernel arguments) and
+// their initial state; the last batch adds the sentinel descriptor that closes the chunk ranges.
+__device__ __forceinline__ void store_segments(const SegBatch& b, SegDesc* __restrict__ seg,
+                                               SegState* __restrict__ st) {
   for (int i = threadIdx.x; i < b.count; i += kThreads) {
     seg[b.first + i] = b.d[i];
     SegState s;
@@ -288,6 +280,27 @@ __global__ __launch_bounds__(kThreads) void seg_setup_kernel(SegBatch b, SegDesc
     z.hchunk_base = b.total_hchunks;
     seg[b.m] = z;
   }
+}
+
+// Writes one batch of segment descriptors and their initial state; the first batch also
+// clears the histograms.
+__global__ __launch_bounds__(kThreads) void seg_setup_kernel(SegBatch b, SegDesc* __restrict__ seg,
+                                                             SegState* __restrict__ st,
+                                                             uint32_t* __restrict__ zero_from,
+                                                             size_t zero_count) {
+  if (b.first == 0) {
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < zero_count;
+         i += (size_t)gridDim.x * kThreads)
+      zero_from[i] = 0u;
+  }
+  if (blockIdx.x == 0) store_segments(b, seg, st);
+}
+
+// Clears the histogram area ahead of time (while the host still plans), for the selection that
+// receives its descriptors with the first pass instead of through seg_setup_kernel.
+__global__ __launch_bounds__(kThreads) void zero_words_kernel(uint32_t* __restrict__ p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (size_t)gridDim.x * kThreads)
+    p[i] = 0u;
 }
 
 // Exclusive prefix over the wavefront of a per-lane count in [0, 7], by three ballots.
@@ -488,16 +501,12 @@ __device__ __forceinline__ SegState state_after(SegState* __restrict__ st, int m
 }
 
 // Pass 1 of 3 over the segment: histogram of the top digit (11 bits) of every key.
-template <int HITERS, bool FUSED>
-__global__ __launch_bounds__(kThreads) void hist0_kernel(const float* __restrict__ g,
-                                                         const SegDesc* __restrict__ seg, int m,
-                                                         uint32_t* __restrict__ hist,
-                                                         uint32_t* __restrict__ hmax) {
+template <int HITERS>
+__device__ __forceinline__ void hist0_chunk(const float* __restrict__ g, const SegDesc& d, int j,
+                                            uint32_t* __restrict__ hist, uint32_t* __restrict__ hmax) {
   constexpr int kBins = 1 << kBits0;
   constexpr int kShift = kBits1 + kBits2;
   __shared__ uint32_t lh[kBins];
-  const int j = seg_of_hchunk(seg, m, blockIdx.x);
-  const SegDesc d = seg[j];
   for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
   __syncthreads();
   Chunk<HITERS> ch;
@@ -510,7 +519,6 @@ __global__ __launch_bounds__(kThreads) void hist0_kernel(const float* __restrict
     // key adds itself.  (Aggregating partial matches per key was measured slower than plain
     // adds on Student-t data: 310 vs 270 us on 1.42 GB; this form costs one ballot per 4 keys.)
     const uint32_t d0 = ch.key[i][0] >> kShift;
-#ifndef DEFT_HIST0_PLAIN
     const uint32_t dl = (uint32_t)__builtin_amdgcn_readfirstlane((int)d0);
     const bool same = ch.vmask(i) == 0xF && d0 == dl && (ch.key[i][1] >> kShift) == dl &&
                       (ch.key[i][2] >> kShift) == dl && (ch.key[i][3] >> kShift) == dl;
@@ -518,7 +526,6 @@ __global__ __launch_bounds__(kThreads) void hist0_kernel(const float* __restrict
       if ((threadIdx.x & 63) == 0) atomicAdd(&lh[dl], 256u);
       continue;
     }
-#endif
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       if ((ch.vmask(i) >> c) & 1u) atomicAdd(&lh[ch.key[i][c] >> kShift], 1u);
@@ -536,6 +543,36 @@ __global__ __launch_bounds__(kThreads) void hist0_kernel(const float* __restrict
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) top_bin = max(top_bin, __shfl_down(top_bin, o, 64));
   if ((threadIdx.x & 63) == 0 && top_bin > 0) atomicMax(&hmax[blockIdx.x], (uint32_t)top_bin);
+}
+
+template <int HITERS>
+__global__ __launch_bounds__(kThreads) void hist0_kernel(const float* __restrict__ g,
+                                                         const SegDesc* __restrict__ seg, int m,
+                                                         uint32_t* __restrict__ hist,
+                                                         uint32_t* __restrict__ hmax) {
+  const int j = seg_of_hchunk(seg, m, blockIdx.x);
+  const SegDesc d = seg[j];
+  hist0_chunk<HITERS>(g, d, j, hist, hmax);
+}
+
+// The same pass with the segment descriptors arriving as kernel arguments (all of them: at most
+// kSegBatch segments): workgroup 0 also stores them and the initial states for the later
+// kernels, which saves the separate set-up launch in front of the dependent chain.  The
+// histograms and chunk maxima must have been cleared before (zero_words_kernel).
+template <int HITERS>
+__global__ __launch_bounds__(kThreads) void hist0_inline_kernel(const float* __restrict__ g, SegBatch b,
+                                                                SegDesc* __restrict__ seg,
+                                                                SegState* __restrict__ st,
+                                                                uint32_t* __restrict__ hist,
+                                                                uint32_t* __restrict__ hmax) {
+  int lo = 0, hi = b.count;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (b.d[mid].hchunk_base <= blockIdx.x) lo = mid; else hi = mid;
+  }
+  const SegDesc d = b.d[lo];
+  if (blockIdx.x == 0) store_segments(b, seg, st);
+  hist0_chunk<HITERS>(g, d, lo, hist, hmax);
 }
 
 // Pass 1 for long vectors.  Merging a workgroup's histogram into the segment's costs one
@@ -1269,14 +1306,16 @@ inline uint64_t max_chunks(int64_t elems, int64_t m) {
 // atomics, a fixed cost that wants amortising; count/emit have no such tail and balance better
 // with small chunks.  Each wavefront of a histogram workgroup covers one count/emit chunk.
 template <int ITERS, bool FUSED>
-int launch_select(const float* g, const SegDesc* seg, SegState* st, int m, uint32_t chunks,
+int launch_select(const float* g, SegDesc* seg, SegState* st, int m, uint32_t chunks,
                   uint32_t hchunks, uint32_t* hist, uint32_t* cgt, uint32_t* ceq, uint32_t* obase,
                   uint32_t* ebase, uint32_t* tgt, uint32_t* teq, uint32_t* ccnt, uint32_t* hmax,
                   uint2* slots,
-                  uint32_t cap, bool scan_in_emit,
+                  uint32_t cap, bool scan_in_emit, const SegBatch* inline_batch,
                   int32_t* idx_out, float* val_out, hipStream_t s) {
-  if (FUSED) {
-    hist0_kernel<4 * ITERS, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, m, hist, hmax);
+  if (FUSED && inline_batch) {
+    hist0_inline_kernel<4 * ITERS><<<hchunks, kThreads, 0, s>>>(g, *inline_batch, seg, st, hist, hmax);
+  } else if (FUSED) {
+    hist0_kernel<4 * ITERS><<<hchunks, kThreads, 0, s>>>(g, seg, m, hist, hmax);
   } else {
     // hmax[hchunks] is the chunk counter (zeroed with the histograms by seg_setup_kernel)
     hist0_stream_kernel<4 * ITERS><<<std::min<uint32_t>(hchunks, kStreamGrid), kThreads, 0, s>>>(
@@ -1311,9 +1350,22 @@ int launch_select(const float* g, const SegDesc* seg, SegState* st, int m, uint3
   return DEFT_OK;
 }
 
-// Enqueue the selection of `m` validated, non-empty segments (k >= 1 each).
+// A workspace layout fixed ahead of the plan (sized for m_cap segments and chunks_cap chunks)
+// whose histogram area has already been cleared on the stream.
+struct Precleared {
+  int64_t m_cap;
+  uint64_t chunks_cap;
+};
+
+// Words to clear for a layout: the histograms, the per-chunk maxima and the chunk counter.
+inline size_t clear_words(const SelectLayout& w) { return (w.cgt - w.hist) / sizeof(uint32_t); }
+
+// Enqueue the selection of `m` validated, non-empty segments (k >= 1 each).  With `pre`, short
+// selections of at most kSegBatch segments skip the set-up launch: the descriptors travel with
+// the first pass.
 int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t share,
-               int32_t* idx_out, float* val_out, void* ws, size_t ws_bytes, hipStream_t s) {
+               int32_t* idx_out, float* val_out, void* ws, size_t ws_bytes, hipStream_t s,
+               const Precleared* pre = nullptr) {
   const int m = (int)segs_in.size();
   if (m == 0) return DEFT_OK;
   const int iters = chunk_iters_for(share);
@@ -1337,25 +1389,32 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   uint64_t total_k = 0;
   for (const auto& d : segs) total_k += d.k;
   const uint32_t cap = slot_cap_for(total_k, (uint64_t)share, ce);
-  const SelectLayout w = select_layout(m, chunks, cap);
+  const bool inline_segs = pre && small && m <= kSegBatch && m <= pre->m_cap && chunks <= pre->chunks_cap;
+  const SelectLayout w = inline_segs ? select_layout(pre->m_cap, pre->chunks_cap, cap) : select_layout(m, chunks, cap);
   if (w.total > ws_bytes) return DEFT_EWS;
   char* base = static_cast<char*>(ws);
   SegDesc* seg = reinterpret_cast<SegDesc*>(base + w.seg);
   SegState* st = reinterpret_cast<SegState*>(base + w.st);
   uint32_t* hist = reinterpret_cast<uint32_t*>(base + w.hist);
-  // histograms, the per-chunk maxima and the chunk counter of the long-vector first pass
-  const size_t nzero = (size_t)kHistStride * m + hchunks + 1;
-  const unsigned setup_blocks = (unsigned)std::min<size_t>((nzero + 4 * kThreads - 1) / (4 * kThreads), 256);
-  for (int first = 0; first < m; first += kSegBatch) {
-    SegBatch b;
-    b.first = first;
-    b.count = std::min(kSegBatch, m - first);
-    b.total_chunks = (uint32_t)chunks;
-    b.total_hchunks = (uint32_t)hchunks;
-    b.m = m;
-    b.pad = 0;
-    std::memcpy(b.d, segs.data() + first, sizeof(SegDesc) * (size_t)b.count);
-    seg_setup_kernel<<<first == 0 ? setup_blocks : 1, kThreads, 0, s>>>(b, seg, st, hist, nzero);
+  SegBatch b;
+  b.total_chunks = (uint32_t)chunks;
+  b.total_hchunks = (uint32_t)hchunks;
+  b.m = m;
+  b.pad = 0;
+  if (inline_segs) {
+    b.first = 0;
+    b.count = m;
+    std::memcpy(b.d, segs.data(), sizeof(SegDesc) * (size_t)m);
+  } else {
+    // histograms, the per-chunk maxima and the chunk counter of the long-vector first pass
+    const size_t nzero = (size_t)kHistStride * m + hchunks + 1;
+    const unsigned setup_blocks = (unsigned)std::min<size_t>((nzero + 4 * kThreads - 1) / (4 * kThreads), 256);
+    for (int first = 0; first < m; first += kSegBatch) {
+      b.first = first;
+      b.count = std::min(kSegBatch, m - first);
+      std::memcpy(b.d, segs.data() + first, sizeof(SegDesc) * (size_t)b.count);
+      seg_setup_kernel<<<first == 0 ? setup_blocks : 1, kThreads, 0, s>>>(b, seg, st, hist, nzero);
+    }
   }
   uint32_t* cgt = reinterpret_cast<uint32_t*>(base + w.cgt);
   uint32_t* ceq = reinterpret_cast<uint32_t*>(base + w.ceq);
@@ -1369,10 +1428,10 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   if (small)
     return launch_select<DEFT_SEL_ITERS_SMALL, true>(
         g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, tg, te, cc, hm, sl, cap,
-        scan_in_emit, idx_out, val_out, s);
+        scan_in_emit, inline_segs ? &b : nullptr, idx_out, val_out, s);
   return launch_select<DEFT_SEL_ITERS_LARGE, false>(
       g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, tg, te, cc, hm, sl, cap,
-      scan_in_emit, idx_out, val_out, s);
+      scan_in_emit, nullptr, idx_out, val_out, s);
 }
 
 }  // namespace
@@ -1452,11 +1511,11 @@ extern "C" int deft_gather_zero(float* acc_dev, int64_t N, const int32_t* idx_de
   return DEFT_OK;
 }
 
-extern "C" int deft_select(const float* g_dev, int64_t N, const int64_t* offsets_host,
-                           const int64_t* k_host, int32_t L, const int32_t* my_layers_host,
-                           int32_t my_count, int32_t* idx_out_dev, float* val_out_dev,
-                           int64_t* seg_off_host, int64_t out_cap, void* ws_dev, size_t ws_bytes,
-                           void* stream) {
+namespace {
+int select_layers(const float* g_dev, int64_t N, const int64_t* offsets_host, const int64_t* k_host,
+                  int32_t L, const int32_t* my_layers_host, int32_t my_count, int32_t* idx_out_dev,
+                  float* val_out_dev, int64_t* seg_off_host, int64_t out_cap, void* ws_dev,
+                  size_t ws_bytes, void* stream, const Precleared* pre) {
   if (!g_dev || !offsets_host || !k_host || !seg_off_host || my_count < 0 || out_cap < 0)
     return DEFT_EINVAL;
   if (my_count > 0 && !my_layers_host) return DEFT_EINVAL;
@@ -1496,10 +1555,20 @@ extern "C" int deft_select(const float* g_dev, int64_t N, const int64_t* offsets
     if (ws_bytes < deft_workspace_bytes(DEFT_OP_SELECT, share, (int32_t)segs.size())) return DEFT_EWS;
   }
   const int rc = run_select(g_dev, segs, share, idx_out_dev, val_out_dev, ws_dev, ws_bytes,
-                            static_cast<hipStream_t>(stream));
+                            static_cast<hipStream_t>(stream), pre);
   if (rc != DEFT_OK) return rc;
   std::copy(seg_off.begin(), seg_off.end(), seg_off_host);
   return DEFT_OK;
+}
+}  // namespace
+
+extern "C" int deft_select(const float* g_dev, int64_t N, const int64_t* offsets_host,
+                           const int64_t* k_host, int32_t L, const int32_t* my_layers_host,
+                           int32_t my_count, int32_t* idx_out_dev, float* val_out_dev,
+                           int64_t* seg_off_host, int64_t out_cap, void* ws_dev, size_t ws_bytes,
+                           void* stream) {
+  return select_layers(g_dev, N, offsets_host, k_host, L, my_layers_host, my_count, idx_out_dev,
+                       val_out_dev, seg_off_host, out_cap, ws_dev, ws_bytes, stream, nullptr);
 }
 
 extern "C" int topk_global(const float* g_dev, int64_t N, int64_t K, int32_t* idx_out_dev,
@@ -1599,6 +1668,19 @@ extern "C" int deft_sparsify(const deft_job* job, const float* g_dev, int64_t it
                  j.ws_bytes, stream);
   if (rc != DEFT_OK) return rc;
   if (norms_done_event) HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(norms_done_event), s));
+  // While the host waits and plans, clear the histogram area of a layout that does not depend on
+  // the plan (the norm pass's partial sums share the workspace: stream order keeps them safe).
+  Precleared pre;
+  pre.m_cap = j.L;
+  pre.chunks_cap = max_chunks(j.N, j.L);
+  {
+    const SelectLayout w = select_layout(pre.m_cap, pre.chunks_cap);
+    const size_t words = clear_words(w);
+    const unsigned blocks = (unsigned)std::min<size_t>((words + 4 * kThreads - 1) / (4 * kThreads), 1024);
+    zero_words_kernel<<<blocks, kThreads, 0, s>>>(
+        reinterpret_cast<uint32_t*>(static_cast<char*>(j.ws_dev) + w.hist), words);
+    HIP_TRY(hipGetLastError());
+  }
   rc = await_sums(j.sumsq_pinned, j.L, s);
   if (rc != DEFT_OK) return rc;
 
@@ -1610,8 +1692,8 @@ extern "C" int deft_sparsify(const deft_job* job, const float* g_dev, int64_t it
   rc = deft_assign_layers(j.sizes_host, j.k_host, j.L, j.n_workers, iteration, j.rank,
                           j.owner_bin_host, j.my_layers_host, &cnt);
   if (rc != DEFT_OK) return rc;
-  rc = deft_select(g_dev, j.N, j.offsets_host, j.k_host, j.L, j.my_layers_host, cnt, j.idx_out_dev,
-                   j.val_out_dev, j.seg_off_host, j.out_cap, j.ws_dev, j.ws_bytes, stream);
+  rc = select_layers(g_dev, j.N, j.offsets_host, j.k_host, j.L, j.my_layers_host, cnt, j.idx_out_dev,
+                     j.val_out_dev, j.seg_off_host, j.out_cap, j.ws_dev, j.ws_bytes, stream, &pre);
   if (rc != DEFT_OK) return rc;
   *my_count_out = cnt;
   *k_r_out = j.seg_off_host[cnt];
