@@ -479,6 +479,11 @@ def test_full_size_configs(deft, name, ranks):
         if r == ranks[0]:  # one rank also against the sorting oracle itself
             o_idx, o_val, _ = O.select(gs.g, off, o_k, o_part)
             assert (idx == o_idx).all() and (_bits(val) == _bits(o_val)).all()
+        # the single entry point (the call the benchmark times) returns the same bits
+        one = sel.sparsify(gd, rank=r)
+        assert one.k.tolist() == o_k and one.my_layers.tolist() == o_part
+        assert one.seg_off.tolist() == res.seg_off.tolist()
+        assert (one.idx == idx).all() and (_bits(one.val) == _bits(val)).all()
     gi, gv = sel.topk_global(gd)
     _verify_topk_by_threshold(gs.g, gi.astype(np.int64), gv, 0, gs.N, sel.K)
 

@@ -84,3 +84,40 @@ def test_random_layers_and_k(deft, seed):
         assert (np.abs(got[nz] - want[nz]) / want[nz]).max(initial=0.0) <= 1e-13
     finally:
         os.environ.pop("DEFT_LONG_VECTOR_ELEMS", None)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_whole_call(deft, seed):
+    """deft_sparsify on random layer lists (fewer and more segments than one descriptor batch
+    holds, both launch shapes) against the oracle's whole path fed the GPU's norms."""
+    rng = np.random.default_rng(9000 + seed)
+    if seed % 4 == 3:
+        os.environ["DEFT_LONG_VECTOR_ELEMS"] = "0"
+    try:
+        n_tensors = int(rng.integers(1, 60)) if seed % 2 else int(rng.integers(150, 260))
+        top = int(10 ** rng.uniform(1, 4.8))
+        sizes = [int(x) for x in rng.integers(1, top + 1, n_tensors)]
+        n = int(rng.integers(1, 5))
+        d = float(10 ** rng.uniform(-3, -0.5))
+        sel = pipeline.DeftSelector(sizes, n, d, DEV)
+        N = sel.N
+        g = _values(rng, N, seed % 6)
+        pos = 0
+        for sz in sizes:  # per-tensor scales, so that the norms differ
+            g[pos:pos + sz] *= np.float32(10 ** rng.uniform(-3, 0))
+            pos += sz
+        gd = torch.from_numpy(g).to(DEV)
+        off, lay = sel.offsets.tolist(), sel.sizes.tolist()
+        for it in range(n):
+            r = int(rng.integers(0, n))
+            res = sel.sparsify(gd, rank=r, iteration=it)
+            k = O.alloc_k(res.norms, lay, N, d)
+            assert res.k.tolist() == k
+            owner, part, _ = O.assign_layers(lay, k, n, it, r)
+            assert res.owner_bin.tolist() == owner and res.my_layers.tolist() == part
+            o_idx, o_val, o_seg = O.select(g, off, k, part)
+            assert res.seg_off.tolist() == o_seg.tolist()
+            assert res.idx.tolist() == o_idx.tolist()
+            assert (res.val.view(np.uint32) == o_val.view(np.uint32)).all()
+    finally:
+        os.environ.pop("DEFT_LONG_VECTOR_ELEMS", None)
