@@ -6,16 +6,18 @@
 // reductions/ballots, per-workgroup LDS histograms, no matrix instructions.
 //
 // Selection = exact radix select on the 31-bit key (bits & 0x7fffffff), digit levels of
-// 11/10/10 bits, in three passes over a segment, then an ordered compaction:
+// 11/10/10 bits.  The segment is read once in full and a second time where it can still hold
+// selected entries; the rest works on a few hundred parked bytes per chunk:
 //   hist0        pass 1: histogram of the top digit; largest top digit of every chunk
-//   pass2        pass 2: counts keys above the threshold's top-digit bucket, histograms the
-//                bucket's keys on the second digit and parks their low 20 bits in per-chunk slots
+//   pass2        pass 2: skips chunks below the threshold's top-digit bucket; parks every key at
+//                or above that bucket as {value bits, index}, in index order, in per-chunk slots;
+//                histograms the bucket's keys on the second digit
 //   slot_hist2   third digit level, from the slots
 //   slot_count   per-chunk counts of keys > T and == T, from the slots
-//   emit         pass 3: ordered (index, value) write
+//   emit         ordered (index, value) write, from the slots
+// A chunk whose slots overflowed is read from the segment again by the three slot kernels.
 // The bucket search between levels runs inside the next kernel (short vectors) or as a
-// one-workgroup-per-segment kernel (long vectors).  Passes 2 and 3 skip chunks that cannot
-// hold a selected entry.
+// one-workgroup-per-segment kernel (long vectors).
 // An element is selected iff key > T, or key == T and fewer than r equal keys precede it in
 // its segment.  Every pass walks the segments in fixed-size chunks; a chunk never spans two
 // segments, so small layers simply own short chunks and large layers are split over many
