@@ -264,6 +264,19 @@ int deft_sparsify(const deft_job* job, const float* g_dev, int64_t iteration, vo
                   void* norms_done_event, int32_t* my_count_out, int64_t* k_r_out);
 
 /*
+ * Alg. 1, the accumulation step and the sparsifier call that follows it, as a single entry
+ * point: acc = e + eta * grad is formed by the norm pass (as deft_accumulate_norms: fp32,
+ * product rounded, then sum rounded) and the selection then runs on acc, exactly as
+ * deft_sparsify(job, acc_dev, ...) would after deft_accumulate_norms.
+ *   e_dev, grad_dev  in   N floats each, device, 16-byte aligned
+ *   acc_dev          out  N floats, device, 16-byte aligned; may be the same buffer as e_dev
+ * Other arguments, blocking behaviour and errors: as deft_sparsify.
+ */
+int deft_accumulate_sparsify(const deft_job* job, const float* e_dev, const float* grad_dev,
+                             float eta, float* acc_dev, int64_t iteration, void* stream,
+                             void* norms_done_event, int32_t* my_count_out, int64_t* k_r_out);
+
+/*
  * Upper bound on the scratch bytes of a device call.
  *   DEFT_OP_NORMS:        elems = N,            count = L
  *   DEFT_OP_SELECT:       elems = total size of the selected layers (N always suffices),

@@ -38,6 +38,7 @@ SIGNATURES = {
     "topk_global": (C.c_int, [_P, C.c_int64, C.c_int64, _P, _P, _P, C.c_size_t, _P]),
     "deft_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int64, C.c_int32]),
     "deft_sparsify": (C.c_int, [_P, _P, C.c_int64, _P, _P, _P, _P]),
+    "deft_accumulate_sparsify": (C.c_int, [_P, _P, _P, C.c_float, _P, C.c_int64, _P, _P, _P, _P]),
 }
 
 _lib = None
@@ -213,4 +214,17 @@ def deft_sparsify(job: DeftJob, g, iteration: int, stream=None, norms_done_event
     _check(lib().deft_sparsify(C.addressof(job), g.data_ptr(), int(iteration), _stream(stream),
                                int(norms_done_event), C.addressof(cnt), C.addressof(kr)),
            "deft_sparsify")
+    return int(cnt.value), int(kr.value)
+
+
+def deft_accumulate_sparsify(job: DeftJob, e, grad, eta: float, acc, iteration: int, stream=None,
+                             norms_done_event: int = 0):
+    """acc = e + eta*grad, then the whole sparsifier call on acc; returns (my_count, k_r)."""
+    cnt = C.c_int32(0)
+    kr = C.c_int64(0)
+    _check(lib().deft_accumulate_sparsify(C.addressof(job), e.data_ptr(), grad.data_ptr(),
+                                          float(eta), acc.data_ptr(), int(iteration),
+                                          _stream(stream), int(norms_done_event),
+                                          C.addressof(cnt), C.addressof(kr)),
+           "deft_accumulate_sparsify")
     return int(cnt.value), int(kr.value)

@@ -1638,10 +1638,17 @@ int await_sums(const double* sumsq_pinned, int32_t L, hipStream_t s) {
 }
 }  // namespace
 
-extern "C" int deft_sparsify(const deft_job* job, const float* g_dev, int64_t iteration,
-                             void* stream, void* norms_done_event, int32_t* my_count_out,
-                             int64_t* k_r_out) {
-  if (!job || !g_dev || !my_count_out || !k_r_out) return DEFT_EINVAL;
+namespace {
+// The whole call.  Plain: the vector `src` is normed and selected from.  Accumulating (grad and
+// acc given): acc = src + eta * grad is formed by the norm pass and selected from.
+int sparsify(const deft_job* job, const float* src, const float* grad, float eta, float* acc,
+             int64_t iteration, void* stream, void* norms_done_event, int32_t* my_count_out,
+             int64_t* k_r_out) {
+  const float* g_dev = acc ? acc : src;  // what the selection reads
+  if (!job || !src || !my_count_out || !k_r_out) return DEFT_EINVAL;
+  if (acc && (!grad || (reinterpret_cast<uintptr_t>(grad) & 15u) ||
+              (reinterpret_cast<uintptr_t>(src) & 15u)))
+    return DEFT_EINVAL;
   const deft_job& j = *job;
   if (!j.offsets_host || !j.offsets_dev || !j.sizes_host || !j.sumsq_pinned || !j.norms_host ||
       !j.k_host || !j.owner_bin_host || !j.my_layers_host || !j.seg_off_host || !j.ws_dev)
@@ -1666,8 +1673,8 @@ extern "C" int deft_sparsify(const deft_job* job, const float* g_dev, int64_t it
   volatile uint64_t* arm = reinterpret_cast<volatile uint64_t*>(j.sumsq_pinned);
   for (int32_t l = 0; l < j.L; ++l) arm[l] = kSumUnset;
   std::atomic_thread_fence(std::memory_order_seq_cst);
-  rc = run_norms(g_dev, nullptr, 0.0f, nullptr, j.N, j.offsets_dev, j.L, j.sumsq_pinned, j.ws_dev,
-                 j.ws_bytes, stream);
+  rc = run_norms(src, grad, eta, acc, j.N, j.offsets_dev, j.L, j.sumsq_pinned, j.ws_dev, j.ws_bytes,
+                 stream);
   if (rc != DEFT_OK) return rc;
   if (norms_done_event) HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(norms_done_event), s));
   // While the host waits and plans, clear the histogram area of a layout that does not depend on
@@ -1700,4 +1707,21 @@ extern "C" int deft_sparsify(const deft_job* job, const float* g_dev, int64_t it
   *my_count_out = cnt;
   *k_r_out = j.seg_off_host[cnt];
   return DEFT_OK;
+}
+}  // namespace
+
+extern "C" int deft_sparsify(const deft_job* job, const float* g_dev, int64_t iteration,
+                             void* stream, void* norms_done_event, int32_t* my_count_out,
+                             int64_t* k_r_out) {
+  return sparsify(job, g_dev, nullptr, 0.0f, nullptr, iteration, stream, norms_done_event,
+                  my_count_out, k_r_out);
+}
+
+extern "C" int deft_accumulate_sparsify(const deft_job* job, const float* e_dev,
+                                        const float* grad_dev, float eta, float* acc_dev,
+                                        int64_t iteration, void* stream, void* norms_done_event,
+                                        int32_t* my_count_out, int64_t* k_r_out) {
+  if (!grad_dev || !acc_dev) return DEFT_EINVAL;
+  return sparsify(job, e_dev, grad_dev, eta, acc_dev, iteration, stream, norms_done_event,
+                  my_count_out, k_r_out);
 }

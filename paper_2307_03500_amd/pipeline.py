@@ -177,6 +177,23 @@ class DeftSelector:
                          self.mine_h[:cnt].copy(), self.seg_h[:cnt + 1].copy(),
                          self.idx_out[:kr], self.val_out[:kr], {"step_ms": (t1 - t0) * 1e3})
 
+    def accumulate_sparsify(self, e: torch.Tensor, grad: torch.Tensor, eta: float,
+                            acc: torch.Tensor, rank: int, iteration: int = 0) -> Selection:
+        """Alg. 1's accumulation and the sparsifier call on its result, one library entry."""
+        for t in (e, grad, acc):
+            assert t.dtype == torch.float32 and t.numel() == self.N and t.device == self.device
+        st = torch.cuda.current_stream()
+        rc = self._lib.deft_accumulate_sparsify(self._job(rank), e.data_ptr(), grad.data_ptr(),
+                                                float(eta), acc.data_ptr(), iteration,
+                                                st.cuda_stream, 0, self._cnt_p, self._kr_p)
+        if rc:
+            raise B.DeftError(rc, "deft_accumulate_sparsify")
+        st.synchronize()
+        cnt, kr = self._cnt_c.value, self._kr_c.value
+        return Selection(self.norms_h.copy(), self.k_h.copy(), self.owner_h.copy(),
+                         self.mine_h[:cnt].copy(), self.seg_h[:cnt + 1].copy(),
+                         self.idx_out[:kr], self.val_out[:kr])
+
     def select_with_plan(self, g: torch.Tensor, k: np.ndarray, my_layers: np.ndarray):
         """Alg. 5 alone, for a given (k, layer list)."""
         seg = B.deft_select(g, self.offsets, k, my_layers, self.idx_out, self.val_out, self.ws)

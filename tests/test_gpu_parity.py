@@ -427,6 +427,52 @@ def test_one_error_feedback_iteration_all_workers(deft):
     assert len(np.unique(o_idx)) == len(o_idx) == sum(o_k)  # density kept, no build-up (Sec. 4.3)
 
 
+@pytest.mark.parametrize("in_place", [False, True])
+def test_accumulate_sparsify_two_iterations(deft, in_place):
+    """Two iterations of Alg. 1 on one worker through the fused entry (accumulate + norms ->
+    plan -> select), the second carrying the first one's error; the other workers' picks are
+    zeroed too, as after the exchange.  Everything against the oracle, bit for bit."""
+    gs = synth.make("lstm_lm", seed=5)
+    n, d, N = gs.n_workers, gs.d, gs.N
+    sel = _selector(deft, gs.tensor_sizes, n, d)
+    off, lay = sel.offsets.tolist(), sel.sizes.tolist()
+    rng = np.random.default_rng(11)
+    e = (rng.standard_normal(N) * 1e-3).astype(np.float32)
+    e_d = torch.from_numpy(e).to(DEV)
+    acc_d = e_d if in_place else torch.empty_like(e_d)
+    o_e = e.copy()
+    for it in range(2):
+        grad = np.roll(gs.g, 1000 * it + 1) if it else gs.g
+        grad_d = torch.from_numpy(np.ascontiguousarray(grad)).to(DEV)
+        eta = 0.1 / (it + 1)
+        r = (3 * it + 2) % n
+        res = sel.accumulate_sparsify(e_d, grad_d, eta, acc_d, rank=r, iteration=it)
+        o_acc = O.accumulate(o_e, grad, eta)
+        assert (_bits(acc_d.cpu().numpy()) == _bits(o_acc)).all()
+        o_norms = O.layer_norms(o_acc, off)
+        _check_norms(res.norms, o_norms)
+        o_k = O.alloc_k(o_norms, lay, N, d)
+        assert res.k.tolist() == o_k
+        o_owner, o_part, _ = O.assign_layers(lay, o_k, n, it, r)
+        assert res.owner_bin.tolist() == o_owner and res.my_layers.tolist() == o_part
+        o_idx, o_val, o_seg = O.select(o_acc, off, o_k, o_part)
+        assert res.seg_off.tolist() == o_seg.tolist()
+        assert res.idx.tolist() == o_idx.tolist() and (_bits(res.val) == _bits(o_val)).all()
+        # the exchange: every worker's picks (here computed by the oracle) leave the accumulator
+        all_idx = np.concatenate([O.select(o_acc, off, o_k, O.assign_layers(lay, o_k, n, it, q)[1])[0]
+                                  for q in range(n)]).astype(np.int32)
+        idx_d = torch.from_numpy(all_idx).to(DEV)
+        vals_d = torch.empty(idx_d.numel(), dtype=torch.float32, device=DEV)
+        deft.deft_gather_zero(acc_d, idx_d, vals_d)
+        torch.cuda.synchronize()
+        o_vals, o_e = O.gather_zero(o_acc, all_idx)
+        assert (_bits(vals_d.cpu().numpy()) == _bits(o_vals)).all()
+        assert (_bits(acc_d.cpu().numpy()) == _bits(o_e)).all()
+        if not in_place:
+            e_d.copy_(acc_d)  # e = acc (Alg. 1, last line)
+            torch.cuda.synchronize()
+
+
 def test_gather_zero_edge_cases(deft):
     acc = torch.arange(1, 11, dtype=torch.float32, device=DEV)
     idx = torch.tensor([9, 0, 4, -1, 10], dtype=torch.int32, device=DEV)  # two out of range

@@ -259,6 +259,25 @@ def test_device_calls_reject_bad_arguments_before_touching_the_gpu(deft):
     assert spars(ws_dev=0x4004) == B.DEFT_EINVAL
     assert spars(ws_bytes=64) == B.DEFT_EWS
     assert cnt.value == -7 and kr.value == -7
+    ok_job = B.DeftJob(N=16, L=2, n_workers=2, rank=0, reserved=0, d=0.25,
+                       offsets_host=off.ctypes.data, offsets_dev=0x5000,
+                       sizes_host=sizes.ctypes.data, sumsq_pinned=0x6000,
+                       norms_host=bufs["norms"].ctypes.data, k_host=bufs["k"].ctypes.data,
+                       owner_bin_host=bufs["owner"].ctypes.data,
+                       my_layers_host=bufs["mine"].ctypes.data, seg_off_host=bufs["seg"].ctypes.data,
+                       idx_out_dev=0x2000, val_out_dev=0x3000, out_cap=16, ws_dev=0x4000,
+                       ws_bytes=1 << 20)
+
+    def accsp(e=0x1000, gr=0x7000, acc=0x8000):
+        return lib.deft_accumulate_sparsify(C.addressof(ok_job), C.c_void_p(e), C.c_void_p(gr), 0.5,
+                                            C.c_void_p(acc), 0, None, None, C.addressof(cnt),
+                                            C.addressof(kr))
+
+    assert accsp(gr=0) == B.DEFT_EINVAL
+    assert accsp(acc=0) == B.DEFT_EINVAL
+    assert accsp(e=0) == B.DEFT_EINVAL
+    assert accsp(gr=0x7004) == B.DEFT_EINVAL
+    assert accsp(acc=0x8008) == B.DEFT_EINVAL
 
     def topk(g=0x1000, N=16, K=4, idx=0x2000, val=0x3000, ws=0x4000, wsb=1 << 20):
         return lib.topk_global(C.c_void_p(g), N, K, C.c_void_p(idx), C.c_void_p(val),
