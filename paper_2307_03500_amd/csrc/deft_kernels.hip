@@ -1076,88 +1076,18 @@ __global__ __launch_bounds__(kThreads) void scan_tops_kernel(uint32_t* __restric
   }
 }
 
-// Ordered compaction of one chunk.  Ties are granted in index order until the quota r is used
-// up, so a chunk's first output slot is  out_off + (keys > T before it) + min(r, keys == T
-// before it)  within its segment.  The chunk's selectable keys come from its slots (parked
-// by pass 2 in index order, one thread per entry); only a chunk that overflowed its slots is
-// read from the segment again.  SCAN_HERE: the workgroup sums the counts of the preceding
-// chunks of its segment itself -- cheaper than separate scan launches when every segment is
-// short; otherwise the prefixes come from scan_tiles_kernel / scan_tops_kernel.
-template <int ITERS, bool SCAN_HERE>
-__global__ __launch_bounds__(kThreads) void emit_kernel(
-    const float* __restrict__ g, const SegDesc* __restrict__ seg, const SegState* __restrict__ st,
-    int m, const uint32_t* __restrict__ chunk_gt, const uint32_t* __restrict__ chunk_eq,
-    const uint32_t* __restrict__ pre_gt, const uint32_t* __restrict__ pre_eq,
-    const uint32_t* __restrict__ tile_gt, const uint32_t* __restrict__ tile_eq,
-    const uint32_t* __restrict__ live_cnt, const uint2* __restrict__ slots, uint32_t cap,
-    int32_t* __restrict__ idx_out, float* __restrict__ val_out) {
-  __shared__ uint32_t wtot[2][kWaves];
-  const int j = seg_of_chunk(seg, m, blockIdx.x);
-  const SegDesc d = seg[j];
-  const uint32_t T = st[(size_t)3 * m + j].T, r = st[(size_t)3 * m + j].r;
-  // a chunk that holds nothing to select is not read at all (layers whose magnitudes lie
-  // below the threshold -- most of the vector for the conventional Top-k)
-  const uint32_t cgt = chunk_gt[blockIdx.x], ceq = chunk_eq[blockIdx.x];
-  if (cgt == 0 && ceq == 0) return;
-  uint32_t eb, ob;
-  if (SCAN_HERE) {
-    uint32_t sg = 0, se = 0;
-    for (uint32_t c = d.chunk_base + threadIdx.x; c < blockIdx.x; c += kThreads) {
-      sg += chunk_gt[c];
-      se += chunk_eq[c];
-    }
-    sg = wave_sum_u32(sg);
-    se = wave_sum_u32(se);
-    if ((threadIdx.x & 63) == 0) { wtot[0][threadIdx.x >> 6] = sg; wtot[1][threadIdx.x >> 6] = se; }
-    __syncthreads();
-    const uint32_t gt_before = wtot[0][0] + wtot[0][1] + wtot[0][2] + wtot[0][3];
-    eb = wtot[1][0] + wtot[1][1] + wtot[1][2] + wtot[1][3];
-    ob = d.out_off + gt_before + min(r, eb);
-    __syncthreads();
-  } else {
-    // global prefixes (tile base + tile-local); the segment's own prefix is a difference
-    const uint32_t c = blockIdx.x, c0 = d.chunk_base;
-    const uint32_t gt_before = (tile_gt[c / kScanTile] + pre_gt[c]) - (tile_gt[c0 / kScanTile] + pre_gt[c0]);
-    eb = (tile_eq[c / kScanTile] + pre_eq[c]) - (tile_eq[c0 / kScanTile] + pre_eq[c0]);
-    ob = d.out_off + gt_before + min(r, eb);
-  }
-  if (cgt == 0 && eb >= r) return;  // only ties here, and the quota was used up before them
-  // 0: none of the chunk's ties is taken, 1: all are, 2: the quota ends inside this chunk
-  const int mode = (eb >= r) ? 0 : ((r - eb >= ceq) ? 1 : 2);
+// Ordered compaction of one chunk read from the segment itself (a chunk whose slots overflowed),
+// by the whole workgroup.  ob: the chunk's first output position; eb: ties in the segment's
+// earlier chunks; mode 0: none of the chunk's ties is taken, 1: all are, 2: the quota r ends
+// inside this chunk and its ties are ranked in index order.
+template <int ITERS>
+__device__ __forceinline__ void emit_from_segment(
+    const float* __restrict__ g, const SegDesc& d, uint32_t local_chunk, uint32_t T, uint32_t r,
+    uint32_t eb, uint32_t ob, int mode, uint32_t lim, int32_t* __restrict__ idx_out,
+    float* __restrict__ val_out, uint32_t (*wtot)[kWaves]) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const uint32_t lim = d.out_off + d.k;  // a segment never writes past its own k slots
-  const uint32_t n_live = live_cnt[blockIdx.x];
-  if (n_live <= cap) {
-    const bool on = threadIdx.x < n_live;
-    const uint2 e = on ? slots[(size_t)blockIdx.x * cap + threadIdx.x] : make_uint2(0u, 0u);
-    const uint32_t key = e.x & 0x7FFFFFFFu;
-    const bool is_eq = on && key == T;
-    bool take = on && key > T;
-    const unsigned long long below = (1ull << lane) - 1ull;
-    if (mode == 1) {
-      take = take || is_eq;
-    } else if (mode == 2) {
-      // the quota ends inside this chunk: rank its ties in index order
-      const unsigned long long eqb = __ballot(is_eq);
-      if (lane == 0) wtot[1][wave] = (uint32_t)__popcll(eqb);
-      __syncthreads();
-      uint32_t rank = eb + (uint32_t)__popcll(eqb & below);
-      for (int w = 0; w < wave; ++w) rank += wtot[1][w];
-      take = take || (is_eq && rank < r);
-    }
-    const unsigned long long tb = __ballot(take);
-    if (lane == 0) wtot[0][wave] = (uint32_t)__popcll(tb);
-    __syncthreads();
-    uint32_t pos = ob + (uint32_t)__popcll(tb & below);
-    for (int w = 0; w < wave; ++w) pos += wtot[0][w];
-    if (take && pos < lim) {
-      idx_out[pos] = (int32_t)e.y;
-      val_out[pos] = __uint_as_float(e.x);
-    }
-    return;
-  }
   Chunk<ITERS> ch;
-  ch.load(g, d.start, (int64_t)d.start + d.size, blockIdx.x - d.chunk_base);
+  ch.load(g, d.start, (int64_t)d.start + d.size, local_chunk);
 
   uint32_t sel[ITERS];  // 4-bit masks of selected components
   if (mode != 2) {
@@ -1230,6 +1160,156 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(
       }
     }
     pos += tot;
+  }
+}
+
+// Ordered compaction of one chunk per workgroup (short vectors).  Ties are granted in index
+// order until the quota r is used up, so a chunk's first output slot is  out_off + (keys > T
+// before it) + min(r, keys == T before it)  within its segment; the workgroup sums the counts
+// of the preceding chunks of its segment itself -- cheaper than separate scan launches when
+// every segment is short.  The chunk's selectable keys come from its slots (parked by pass 2
+// in index order, one thread per entry); only a chunk that overflowed its slots is read from
+// the segment again.
+template <int ITERS>
+__global__ __launch_bounds__(kThreads) void emit_kernel(
+    const float* __restrict__ g, const SegDesc* __restrict__ seg, const SegState* __restrict__ st,
+    int m, const uint32_t* __restrict__ chunk_gt, const uint32_t* __restrict__ chunk_eq,
+    const uint32_t* __restrict__ live_cnt, const uint2* __restrict__ slots, uint32_t cap,
+    int32_t* __restrict__ idx_out, float* __restrict__ val_out) {
+  __shared__ uint32_t wtot[2][kWaves];
+  const int j = seg_of_chunk(seg, m, blockIdx.x);
+  const SegDesc d = seg[j];
+  const uint32_t T = st[(size_t)3 * m + j].T, r = st[(size_t)3 * m + j].r;
+  // a chunk that holds nothing to select is not read at all
+  const uint32_t cgt = chunk_gt[blockIdx.x], ceq = chunk_eq[blockIdx.x];
+  if (cgt == 0 && ceq == 0) return;
+  uint32_t sg = 0, se = 0;
+  for (uint32_t c = d.chunk_base + threadIdx.x; c < blockIdx.x; c += kThreads) {
+    sg += chunk_gt[c];
+    se += chunk_eq[c];
+  }
+  sg = wave_sum_u32(sg);
+  se = wave_sum_u32(se);
+  if ((threadIdx.x & 63) == 0) { wtot[0][threadIdx.x >> 6] = sg; wtot[1][threadIdx.x >> 6] = se; }
+  __syncthreads();
+  const uint32_t gt_before = wtot[0][0] + wtot[0][1] + wtot[0][2] + wtot[0][3];
+  const uint32_t eb = wtot[1][0] + wtot[1][1] + wtot[1][2] + wtot[1][3];
+  const uint32_t ob = d.out_off + gt_before + min(r, eb);
+  __syncthreads();
+  if (cgt == 0 && eb >= r) return;  // only ties here, and the quota was used up before them
+  const int mode = (eb >= r) ? 0 : ((r - eb >= ceq) ? 1 : 2);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t lim = d.out_off + d.k;  // a segment never writes past its own k slots
+  const uint32_t n_live = live_cnt[blockIdx.x];
+  if (n_live > cap) {
+    emit_from_segment<ITERS>(g, d, blockIdx.x - d.chunk_base, T, r, eb, ob, mode, lim, idx_out,
+                             val_out, wtot);
+    return;
+  }
+  const bool on = threadIdx.x < n_live;
+  const uint2 e = on ? slots[(size_t)blockIdx.x * cap + threadIdx.x] : make_uint2(0u, 0u);
+  const uint32_t key = e.x & 0x7FFFFFFFu;
+  const bool is_eq = on && key == T;
+  bool take = on && key > T;
+  const unsigned long long below = (1ull << lane) - 1ull;
+  if (mode == 1) {
+    take = take || is_eq;
+  } else if (mode == 2) {
+    const unsigned long long eqb = __ballot(is_eq);
+    if (lane == 0) wtot[1][wave] = (uint32_t)__popcll(eqb);
+    __syncthreads();
+    uint32_t rank = eb + (uint32_t)__popcll(eqb & below);
+    for (int w = 0; w < wave; ++w) rank += wtot[1][w];
+    take = take || (is_eq && rank < r);
+  }
+  const unsigned long long tb = __ballot(take);
+  if (lane == 0) wtot[0][wave] = (uint32_t)__popcll(tb);
+  __syncthreads();
+  uint32_t pos = ob + (uint32_t)__popcll(tb & below);
+  for (int w = 0; w < wave; ++w) pos += wtot[0][w];
+  if (take && pos < lim) {
+    idx_out[pos] = (int32_t)e.y;
+    val_out[pos] = __uint_as_float(e.x);
+  }
+}
+
+// The same for long vectors: one wavefront per chunk, so that the many chunks that hold nothing
+// cost a wavefront's two loads instead of a workgroup (32 -> 12 us on a 1.4 GB vector, where
+// three quarters of the chunks are empty); chunk prefixes come from scan_tiles_kernel /
+// scan_tops_kernel (tile base + tile-local; a segment's own prefix is a difference).  Chunks
+// that overflowed their slots are then handled by the whole workgroup, one at a time.
+template <int ITERS>
+__global__ __launch_bounds__(kThreads) void emit_wave_kernel(
+    const float* __restrict__ g, const SegDesc* __restrict__ seg, const SegState* __restrict__ st,
+    int m, uint32_t chunks, const uint32_t* __restrict__ chunk_gt,
+    const uint32_t* __restrict__ chunk_eq, const uint32_t* __restrict__ pre_gt,
+    const uint32_t* __restrict__ pre_eq, const uint32_t* __restrict__ tile_gt,
+    const uint32_t* __restrict__ tile_eq, const uint32_t* __restrict__ live_cnt,
+    const uint2* __restrict__ slots, uint32_t cap, int32_t* __restrict__ idx_out,
+    float* __restrict__ val_out) {
+  __shared__ uint32_t wtot[2][kWaves];
+  __shared__ uint32_t ovf[kWaves], ovf_eb[kWaves], ovf_ob[kWaves];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t c = blockIdx.x * kWaves + wave;
+  bool over = false;
+  uint32_t eb = 0, ob = 0;
+  if (c < chunks) {
+    const uint32_t cgt = chunk_gt[c], ceq = chunk_eq[c];
+    if (cgt != 0 || ceq != 0) {
+      const int j = seg_of_chunk(seg, m, c);
+      const SegDesc d = seg[j];
+      const uint32_t T = st[(size_t)3 * m + j].T, r = st[(size_t)3 * m + j].r;
+      const uint32_t c0 = d.chunk_base;
+      const uint32_t gt_before = (tile_gt[c / kScanTile] + pre_gt[c]) - (tile_gt[c0 / kScanTile] + pre_gt[c0]);
+      eb = (tile_eq[c / kScanTile] + pre_eq[c]) - (tile_eq[c0 / kScanTile] + pre_eq[c0]);
+      ob = d.out_off + gt_before + min(r, eb);
+      if (!(cgt == 0 && eb >= r)) {
+        const uint32_t n = live_cnt[c];
+        if (n > cap) {
+          over = true;
+        } else {
+          const int mode = (eb >= r) ? 0 : ((r - eb >= ceq) ? 1 : 2);
+          const uint32_t lim = d.out_off + d.k;
+          const unsigned long long below = (1ull << lane) - 1ull;
+          uint32_t pos = ob, rank = eb;
+          for (uint32_t r0 = 0; r0 < n; r0 += 64) {
+            const bool on = r0 + lane < n;
+            const uint2 e = on ? slots[(size_t)c * cap + r0 + lane] : make_uint2(0u, 0u);
+            const uint32_t key = e.x & 0x7FFFFFFFu;
+            const bool is_eq = on && key == T;
+            bool take = on && key > T;
+            if (mode == 1) {
+              take = take || is_eq;
+            } else if (mode == 2) {
+              const unsigned long long eqb = __ballot(is_eq);
+              take = take || (is_eq && rank + (uint32_t)__popcll(eqb & below) < r);
+              rank += (uint32_t)__popcll(eqb);
+            }
+            const unsigned long long tb = __ballot(take);
+            const uint32_t p = pos + (uint32_t)__popcll(tb & below);
+            if (take && p < lim) {
+              idx_out[p] = (int32_t)e.y;
+              val_out[p] = __uint_as_float(e.x);
+            }
+            pos += (uint32_t)__popcll(tb);
+          }
+        }
+      }
+    }
+  }
+  if (lane == 0) { ovf[wave] = over ? 1u : 0u; ovf_eb[wave] = eb; ovf_ob[wave] = ob; }
+  __syncthreads();
+  for (int q = 0; q < kWaves; ++q) {
+    if (!ovf[q]) continue;
+    const uint32_t cq = blockIdx.x * kWaves + q;
+    const int j = seg_of_chunk(seg, m, cq);
+    const SegDesc d = seg[j];
+    const uint32_t T = st[(size_t)3 * m + j].T, r = st[(size_t)3 * m + j].r;
+    const uint32_t ebq = ovf_eb[q], obq = ovf_ob[q], ceq = chunk_eq[cq];
+    const int mode = (ebq >= r) ? 0 : ((r - ebq >= ceq) ? 1 : 2);
+    __syncthreads();  // wtot is reused from one overflowed chunk to the next
+    emit_from_segment<ITERS>(g, d, cq - d.chunk_base, T, r, ebq, obq, mode, d.out_off + d.k, idx_out,
+                             val_out, wtot);
   }
 }
 
@@ -1339,14 +1419,14 @@ int launch_select(const float* g, SegDesc* seg, SegState* st, int m, uint32_t ch
                                                               cap, cgt, ceq);
   }
   if (scan_in_emit) {
-    emit_kernel<ITERS, true><<<chunks, kThreads, 0, s>>>(g, seg, st, m, cgt, ceq, obase, ebase, tgt,
-                                                         teq, ccnt, slots, cap, idx_out, val_out);
+    emit_kernel<ITERS><<<chunks, kThreads, 0, s>>>(g, seg, st, m, cgt, ceq, ccnt, slots, cap, idx_out,
+                                                   val_out);
   } else {
     const uint32_t tiles = (chunks + kScanTile - 1) / kScanTile;
     scan_tiles_kernel<<<tiles, kThreads, 0, s>>>(cgt, ceq, chunks, obase, ebase, tgt, teq);
     scan_tops_kernel<<<1, kThreads, 0, s>>>(tgt, teq, tiles);
-    emit_kernel<ITERS, false><<<chunks, kThreads, 0, s>>>(g, seg, st, m, cgt, ceq, obase, ebase, tgt,
-                                                          teq, ccnt, slots, cap, idx_out, val_out);
+    emit_wave_kernel<ITERS><<<(chunks + kWaves - 1) / kWaves, kThreads, 0, s>>>(
+        g, seg, st, m, chunks, cgt, ceq, obase, ebase, tgt, teq, ccnt, slots, cap, idx_out, val_out);
   }
   HIP_TRY(hipGetLastError());
   return DEFT_OK;
