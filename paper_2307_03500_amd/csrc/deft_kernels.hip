@@ -1010,8 +1010,8 @@ __global__ __launch_bounds__(kThreads) void slot_count_wave_kernel(
 
 // Exclusive prefix sums of the two per-chunk count arrays over ALL chunks of the launch
 // (segment boundaries are ignored: a segment's own prefix is a difference of two entries).
-// Level 1: one workgroup per tile of kScanTile chunks writes tile-local prefixes and the tile
-// totals; level 2: one workgroup turns the tile totals into tile bases.
+// One workgroup per tile of kScanTile chunks writes tile-local prefixes and the tile totals; the
+// wavefronts of emit_wave_kernel add up the totals of the tiles in front of their chunk.
 constexpr int kScanPer = 8;
 constexpr int kScanTile = kThreads * kScanPer;
 
@@ -1057,23 +1057,6 @@ __global__ __launch_bounds__(kThreads) void scan_tiles_kernel(
     be += e[q];
   }
   if (threadIdx.x == 0) { tile_gt[blockIdx.x] = tg; tile_eq[blockIdx.x] = te; }
-}
-
-__global__ __launch_bounds__(kThreads) void scan_tops_kernel(uint32_t* __restrict__ tile_gt,
-                                                             uint32_t* __restrict__ tile_eq,
-                                                             uint32_t tiles) {
-  __shared__ uint32_t wsum[kWaves];
-  uint32_t carry_g = 0, carry_e = 0;
-  for (uint32_t t0 = 0; t0 < tiles; t0 += kThreads) {
-    const uint32_t t = t0 + threadIdx.x;
-    const uint32_t vg = t < tiles ? tile_gt[t] : 0u, ve = t < tiles ? tile_eq[t] : 0u;
-    uint32_t tg, te;
-    const uint32_t bg = block_excl_scan(vg, wsum, tg);
-    const uint32_t be = block_excl_scan(ve, wsum, te);
-    if (t < tiles) { tile_gt[t] = carry_g + bg; tile_eq[t] = carry_e + be; }
-    carry_g += tg;
-    carry_e += te;
-  }
 }
 
 // Ordered compaction of one chunk read from the segment itself (a chunk whose slots overflowed),
@@ -1234,9 +1217,9 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(
 }
 
 // The same for long vectors: one wavefront per chunk, so that the many chunks that hold nothing
-// cost a wavefront's two loads instead of a workgroup (32 -> 12 us on a 1.4 GB vector, where
-// three quarters of the chunks are empty); chunk prefixes come from scan_tiles_kernel /
-// scan_tops_kernel (tile base + tile-local; a segment's own prefix is a difference).  Chunks
+// cost a wavefront's two loads instead of a workgroup (32 -> 17 us on a 1.4 GB vector, where
+// three quarters of the chunks are empty); chunk prefixes come from scan_tiles_kernel
+// (tile-local prefixes and tile totals; a segment's own prefix is a difference).  Chunks
 // that overflowed their slots are then handled by the whole workgroup, one at a time.
 template <int ITERS>
 __global__ __launch_bounds__(kThreads) void emit_wave_kernel(
@@ -1259,9 +1242,18 @@ __global__ __launch_bounds__(kThreads) void emit_wave_kernel(
       const int j = seg_of_chunk(seg, m, c);
       const SegDesc d = seg[j];
       const uint32_t T = st[(size_t)3 * m + j].T, r = st[(size_t)3 * m + j].r;
+      // prefix inside the segment: tile-local prefixes plus the totals of the tiles between the
+      // segment's first chunk and this one (few: a tile spans 2048 chunks), summed by the lanes
       const uint32_t c0 = d.chunk_base;
-      const uint32_t gt_before = (tile_gt[c / kScanTile] + pre_gt[c]) - (tile_gt[c0 / kScanTile] + pre_gt[c0]);
-      eb = (tile_eq[c / kScanTile] + pre_eq[c]) - (tile_eq[c0 / kScanTile] + pre_eq[c0]);
+      uint32_t sg = 0, se = 0;
+      for (uint32_t t = c0 / kScanTile + lane; t < c / kScanTile; t += 64) {
+        sg += tile_gt[t];
+        se += tile_eq[t];
+      }
+      sg = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_sum_u32(sg));
+      se = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_sum_u32(se));
+      const uint32_t gt_before = sg + pre_gt[c] - pre_gt[c0];
+      eb = se + pre_eq[c] - pre_eq[c0];
       ob = d.out_off + gt_before + min(r, eb);
       if (!(cgt == 0 && eb >= r)) {
         const uint32_t n = live_cnt[c];
@@ -1424,7 +1416,6 @@ int launch_select(const float* g, SegDesc* seg, SegState* st, int m, uint32_t ch
   } else {
     const uint32_t tiles = (chunks + kScanTile - 1) / kScanTile;
     scan_tiles_kernel<<<tiles, kThreads, 0, s>>>(cgt, ceq, chunks, obase, ebase, tgt, teq);
-    scan_tops_kernel<<<1, kThreads, 0, s>>>(tgt, teq, tiles);
     emit_wave_kernel<ITERS><<<(chunks + kWaves - 1) / kWaves, kThreads, 0, s>>>(
         g, seg, st, m, chunks, cgt, ceq, obase, ebase, tgt, teq, ccnt, slots, cap, idx_out, val_out);
   }
