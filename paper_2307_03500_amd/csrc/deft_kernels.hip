@@ -502,7 +502,7 @@ __device__ __forceinline__ SegState state_after(SegState* __restrict__ st, int m
   return s;
 }
 
-// Pass 1 of 3 over the segment: histogram of the top digit (11 bits) of every key.
+// Pass 1 (the one full read of the segment): histogram of the top digit (11 bits) of every key.
 template <int HITERS>
 __device__ __forceinline__ void hist0_chunk(const float* __restrict__ g, const SegDesc& d, int j,
                                             uint32_t* __restrict__ hist, uint32_t* __restrict__ hmax) {
@@ -649,7 +649,7 @@ __global__ __launch_bounds__(kThreads) void hist0_stream_kernel(
   }
 }
 
-// Pass 2 of 3 over the segment.  The top digit b0 of the threshold is known.  Every key that can
+// Pass 2 (the second, partial read).  The top digit b0 of the threshold is known.  Every key that can
 // still be selected -- top digit above b0 (selected for sure) or equal to b0 ("candidates"; the
 // two together are about as many as k) -- is parked with its index in a small per-chunk slot
 // array, in index order; candidates are also histogrammed on their next digit.  The remaining
