@@ -1146,17 +1146,19 @@ __device__ __forceinline__ void emit_from_segment(
   }
 }
 
-// Ordered compaction of one chunk per workgroup (short vectors).  Ties are granted in index
-// order until the quota r is used up, so a chunk's first output slot is  out_off + (keys > T
-// before it) + min(r, keys == T before it)  within its segment; the workgroup sums the counts
-// of the preceding chunks of its segment itself -- cheaper than separate scan launches when
-// every segment is short.  The chunk's selectable keys come from its slots (parked by pass 2
+// Ordered compaction of one chunk per workgroup (short segments, and dense selections).  Ties
+// are granted in index order until the quota r is used up, so a chunk's first output slot is
+// out_off + (keys > T before it) + min(r, keys == T before it)  within its segment.  SCAN_HERE:
+// the workgroup sums the counts of the preceding chunks of its segment itself -- cheaper than a
+// scan launch when every segment is short.  The chunk's selectable keys come from its slots (parked by pass 2
 // in index order, one thread per entry); only a chunk that overflowed its slots is read from
 // the segment again.
-template <int ITERS>
+template <int ITERS, bool SCAN_HERE>
 __global__ __launch_bounds__(kThreads) void emit_kernel(
     const float* __restrict__ g, const SegDesc* __restrict__ seg, const SegState* __restrict__ st,
     int m, const uint32_t* __restrict__ chunk_gt, const uint32_t* __restrict__ chunk_eq,
+    const uint32_t* __restrict__ pre_gt, const uint32_t* __restrict__ pre_eq,
+    const uint32_t* __restrict__ tile_gt, const uint32_t* __restrict__ tile_eq,
     const uint32_t* __restrict__ live_cnt, const uint2* __restrict__ slots, uint32_t cap,
     int32_t* __restrict__ idx_out, float* __restrict__ val_out) {
   __shared__ uint32_t wtot[2][kWaves];
@@ -1166,10 +1168,23 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(
   // a chunk that holds nothing to select is not read at all
   const uint32_t cgt = chunk_gt[blockIdx.x], ceq = chunk_eq[blockIdx.x];
   if (cgt == 0 && ceq == 0) return;
+  // counts in the segment's earlier chunks: summed here (short segments), or tile-local prefixes
+  // from scan_tiles_kernel plus the totals of the tiles in between
   uint32_t sg = 0, se = 0;
-  for (uint32_t c = d.chunk_base + threadIdx.x; c < blockIdx.x; c += kThreads) {
-    sg += chunk_gt[c];
-    se += chunk_eq[c];
+  if (SCAN_HERE) {
+    for (uint32_t c = d.chunk_base + threadIdx.x; c < blockIdx.x; c += kThreads) {
+      sg += chunk_gt[c];
+      se += chunk_eq[c];
+    }
+  } else {
+    for (uint32_t t = d.chunk_base / kScanTile + threadIdx.x; t < blockIdx.x / kScanTile; t += kThreads) {
+      sg += tile_gt[t];
+      se += tile_eq[t];
+    }
+    if (threadIdx.x == 0) {
+      sg += pre_gt[blockIdx.x] - pre_gt[d.chunk_base];
+      se += pre_eq[blockIdx.x] - pre_eq[d.chunk_base];
+    }
   }
   sg = wave_sum_u32(sg);
   se = wave_sum_u32(se);
@@ -1384,7 +1399,7 @@ int launch_select(const float* g, SegDesc* seg, SegState* st, int m, uint32_t ch
                   uint32_t hchunks, uint32_t* hist, uint32_t* cgt, uint32_t* ceq, uint32_t* obase,
                   uint32_t* ebase, uint32_t* tgt, uint32_t* teq, uint32_t* ccnt, uint32_t* hmax,
                   uint2* slots,
-                  uint32_t cap, bool scan_in_emit, const SegBatch* inline_batch,
+                  uint32_t cap, bool scan_in_emit, bool dense, const SegBatch* inline_batch,
                   int32_t* idx_out, float* val_out, hipStream_t s) {
   if (FUSED && inline_batch) {
     hist0_inline_kernel<4 * ITERS><<<hchunks, kThreads, 0, s>>>(g, *inline_batch, seg, st, hist, hmax);
@@ -1411,13 +1426,17 @@ int launch_select(const float* g, SegDesc* seg, SegState* st, int m, uint32_t ch
                                                               cap, cgt, ceq);
   }
   if (scan_in_emit) {
-    emit_kernel<ITERS><<<chunks, kThreads, 0, s>>>(g, seg, st, m, cgt, ceq, ccnt, slots, cap, idx_out,
-                                                   val_out);
+    emit_kernel<ITERS, true><<<chunks, kThreads, 0, s>>>(g, seg, st, m, cgt, ceq, obase, ebase, tgt, teq,
+                                                         ccnt, slots, cap, idx_out, val_out);
   } else {
     const uint32_t tiles = (chunks + kScanTile - 1) / kScanTile;
     scan_tiles_kernel<<<tiles, kThreads, 0, s>>>(cgt, ceq, chunks, obase, ebase, tgt, teq);
-    emit_wave_kernel<ITERS><<<(chunks + kWaves - 1) / kWaves, kThreads, 0, s>>>(
-        g, seg, st, m, chunks, cgt, ceq, obase, ebase, tgt, teq, ccnt, slots, cap, idx_out, val_out);
+    if (dense)  // most chunks hold many picks (and overflow their slots): a workgroup each
+      emit_kernel<ITERS, false><<<chunks, kThreads, 0, s>>>(g, seg, st, m, cgt, ceq, obase, ebase, tgt,
+                                                            teq, ccnt, slots, cap, idx_out, val_out);
+    else
+      emit_wave_kernel<ITERS><<<(chunks + kWaves - 1) / kWaves, kThreads, 0, s>>>(
+          g, seg, st, m, chunks, cgt, ceq, obase, ebase, tgt, teq, ccnt, slots, cap, idx_out, val_out);
   }
   HIP_TRY(hipGetLastError());
   return DEFT_OK;
@@ -1462,6 +1481,8 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   uint64_t total_k = 0;
   for (const auto& d : segs) total_k += d.k;
   const uint32_t cap = slot_cap_for(total_k, (uint64_t)share, ce);
+  // more than a quarter of a slot array per chunk expected on average
+  const bool dense = (double)ce * (double)total_k > 0.25 * kMaxSlotCap * (double)share;
   const bool inline_segs = pre && small && m <= kSegBatch && m <= pre->m_cap && chunks <= pre->chunks_cap;
   const SelectLayout w = inline_segs ? select_layout(pre->m_cap, pre->chunks_cap, cap) : select_layout(m, chunks, cap);
   if (w.total > ws_bytes) return DEFT_EWS;
@@ -1501,10 +1522,10 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   if (small)
     return launch_select<DEFT_SEL_ITERS_SMALL, true>(
         g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, tg, te, cc, hm, sl, cap,
-        scan_in_emit, inline_segs ? &b : nullptr, idx_out, val_out, s);
+        scan_in_emit, dense, inline_segs ? &b : nullptr, idx_out, val_out, s);
   return launch_select<DEFT_SEL_ITERS_LARGE, false>(
       g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, tg, te, cc, hm, sl, cap,
-      scan_in_emit, nullptr, idx_out, val_out, s);
+      scan_in_emit, dense, nullptr, idx_out, val_out, s);
 }
 
 }  // namespace
