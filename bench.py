@@ -164,6 +164,8 @@ def main():
     ap.add_argument("--lib", default="",
                     help="path of another build of libdeft.so to load (measurement variants "
                          "compiled with a -D switch)")
+    ap.add_argument("--event-every", type=int, default=1,
+                    help="record the event pair around the norm pass in every n-th timed step only")
     ap.add_argument("--stepwise", action="store_true",
                     help="time the step-wise calls (deft_layer_norms, stream sync, the three host "
                          "calls, deft_select) instead of the single deft_sparsify entry")
@@ -229,22 +231,25 @@ def main():
     h = stream.cuda_stream
     t0 = time.perf_counter()
     for s in range(args.steps):
-        ev[s][0].record(stream)
+        timed = s % args.event_every == 0
+        if timed:
+            ev[s][0].record(stream)
         if args.stepwise:
             sel.enqueue_norms(g, h)
-            ev[s][1].record(stream)
+            if timed:
+                ev[s][1].record(stream)
             stream.synchronize()
             cnt = sel.plan_host(rank, 0)
             k_r = sel.enqueue_select(g, cnt, h)
             continue
-        cnt, k_r = sel.enqueue_sparsify(g, rank, 0, h, evh[s])
+        cnt, k_r = sel.enqueue_sparsify(g, rank, 0, h, evh[s] if timed else 0)
         # no sync here: the next step's norm pass queues behind this step's selection (same
         # stream, same buffers); the host only waits where the method needs it, for the norms
         # (inside the call).  The K steps are bracketed by synchronisations on both sides.
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    norm_ms = [e[0].elapsed_time(e[1]) for e in ev]
+    norm_ms = [e[0].elapsed_time(e[1]) for i, e in enumerate(ev) if i % args.event_every == 0]
 
     # host plan alone (Alg. 3 + Alg. 4 on the sums just delivered), outside the timed region
     plan_ms = []
