@@ -732,10 +732,11 @@ __global__ __launch_bounds__(kThreads) void slot_hist2_kernel(
   const int j = seg_of_chunk(seg, m, blockIdx.x);
   const SegDesc d = seg[j];
   const uint32_t local = blockIdx.x - d.chunk_base;
-  const SegState s = state_after<2, FUSED>(st, m, j, hist, local == 0, fl);
-  if (s.done) return;
   const uint32_t n = live_cnt[blockIdx.x];
-  if (n == 0) return;
+  // nothing parked here: no need for the state (the segment's first workgroup records it)
+  if (n == 0 && (!FUSED || local != 0)) return;
+  const SegState s = state_after<2, FUSED>(st, m, j, hist, local == 0, fl);
+  if (s.done || n == 0) return;
   uint32_t* gh = hist + (size_t)j * kHistStride + hist_offset(2);
   if (n <= cap) {
     const bool on = threadIdx.x < n;
@@ -798,8 +799,13 @@ __global__ __launch_bounds__(kThreads) void slot_count_kernel(
   const int j = seg_of_chunk(seg, m, blockIdx.x);
   const SegDesc d = seg[j];
   const uint32_t local = blockIdx.x - d.chunk_base;
-  const uint32_t T = state_after<3, FUSED>(st, m, j, hist, local == 0, fl).T;
   const uint32_t n = live_cnt[blockIdx.x];
+  if (n == 0 && (!FUSED || local != 0)) {
+    // nothing parked here: the counts are zero whatever the threshold is
+    if (threadIdx.x == 0) { chunk_gt[blockIdx.x] = 0; chunk_eq[blockIdx.x] = 0; }
+    return;
+  }
+  const uint32_t T = state_after<3, FUSED>(st, m, j, hist, local == 0, fl).T;
   uint32_t gt = 0, eq = 0;
   if (n <= cap) {
     if (threadIdx.x < n) {
