@@ -410,27 +410,37 @@ __host__ __device__ constexpr int hist_offset(int level) {
   return level == 0 ? 0 : (level == 1 ? (1 << kBits0) : (1 << kBits0) + (1 << kBits1));
 }
 
-// Run by one whole workgroup: from the finished histogram `gh` of level LEVEL and the state
-// `s` before that level, locate the bucket holding the k_rem-th largest key of the current
+// Run by one whole workgroup: from the finished histogram of level LEVEL (its bins already
+// loaded, each thread its own) and the state `s` before that level, locate the bucket holding the k_rem-th largest key of the current
 // prefix and return the state after the level (in every thread).  If the bucket is taken
 // entirely, or this was the last level, the threshold is resolved.
+// Bins of a level's histogram owned by a thread of the bucket search: thread t owns the kPer
+// bins just below kBins - t*kPer, i.e. threads walk the buckets from the largest keys down.
 template <int LEVEL>
-__device__ __forceinline__ SegState find_bucket(const uint32_t* __restrict__ gh, SegState s,
+struct LevelBins {
+  static constexpr int kBits = LEVEL == 0 ? kBits0 : (LEVEL == 1 ? kBits1 : kBits2);
+  static constexpr int kBins = 1 << kBits;
+  static constexpr int kPer = kBins / kThreads;
+  uint32_t v[kPer];
+  __device__ __forceinline__ void load(const uint32_t* __restrict__ gh) {
+    const int top = kBins - threadIdx.x * kPer;
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) v[q] = gh[top - 1 - q];
+  }
+};
+
+template <int LEVEL>
+__device__ __forceinline__ SegState find_bucket(const LevelBins<LEVEL>& bins, SegState s,
                                                 uint32_t* __restrict__ lds /* kWaves + 8 words */) {
   constexpr int kBits = LEVEL == 0 ? kBits0 : (LEVEL == 1 ? kBits1 : kBits2);
   constexpr int kRemBits = LEVEL == 0 ? (kBits1 + kBits2) : (LEVEL == 1 ? kBits2 : 0);
   constexpr int kBins = 1 << kBits;
   constexpr int kPer = kBins / kThreads;
-  // thread t owns the kPer bins just below kBins - t*kPer, i.e. threads walk the buckets from
-  // the largest keys down
   const int top = kBins - threadIdx.x * kPer;
-  uint32_t v[kPer];
+  const uint32_t (&v)[kPer] = bins.v;
   uint32_t mine = 0;
 #pragma unroll
-  for (int q = 0; q < kPer; ++q) {
-    v[q] = gh[top - 1 - q];
-    mine += v[q];
-  }
+  for (int q = 0; q < kPer; ++q) mine += v[q];
   // exclusive prefix of `mine` over threads (ascending thread = descending key)
   uint32_t inc = mine;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -495,9 +505,13 @@ __device__ __forceinline__ SegState state_after(SegState* __restrict__ st, int m
                                                 const uint32_t* __restrict__ hist, bool first_block,
                                                 uint32_t* __restrict__ lds) {
   if (!FUSED || LEVEL_DONE == 0) return st[(size_t)LEVEL_DONE * m + j];
-  SegState s = st[(size_t)(LEVEL_DONE - 1) * m + j];
-  if (!s.done)
-    s = find_bucket<LEVEL_DONE - 1>(hist + (size_t)j * kHistStride + hist_offset(LEVEL_DONE - 1), s, lds);
+  constexpr int kPrev = LEVEL_DONE > 0 ? LEVEL_DONE - 1 : 0;
+  // the bins are fetched before the previous state is known (they do not depend on it): one
+  // memory round trip less on the critical path of every workgroup
+  LevelBins<kPrev> bins;
+  bins.load(hist + (size_t)j * kHistStride + hist_offset(kPrev));
+  SegState s = st[(size_t)kPrev * m + j];
+  if (!s.done) s = find_bucket<kPrev>(bins, s, lds);
   if (first_block && threadIdx.x == 0) st[(size_t)LEVEL_DONE * m + j] = s;
   return s;
 }
@@ -670,13 +684,14 @@ __global__ __launch_bounds__(kThreads) void pass2_kernel(
   const int j = seg_of_hchunk(seg, m, blockIdx.x);
   const SegDesc d = seg[j];
   const uint32_t local = blockIdx.x - d.hchunk_base;
+  const uint32_t my_max = hmax[blockIdx.x];  // fetched ahead of the bucket search
+  const uint32_t n_chunks = seg[j + 1].chunk_base - d.chunk_base;
   const SegState s = state_after<1, FUSED>(st, m, j, hist, local == 0, fl);
   const uint32_t b0 = s.done ? (s.T >> (kBits1 + kBits2)) : s.prefix;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const uint32_t n_chunks = seg[j + 1].chunk_base - d.chunk_base;
   const uint32_t ec_local = local * 4 + wave;        // this wave's count/emit chunk
   const bool have_chunk = ec_local < n_chunks;
-  if (hmax[blockIdx.x] < b0) {
+  if (my_max < b0) {
     // every key here lies below the threshold's bucket: nothing to park, no read
     if (lane == 0 && have_chunk) live_cnt[d.chunk_base + ec_local] = 0;
     return;
@@ -782,7 +797,9 @@ __global__ __launch_bounds__(kThreads) void find_kernel(SegState* __restrict__ s
   __shared__ uint32_t fl[kWaves + 8];
   const int j = blockIdx.x;
   SegState s = st[(size_t)LEVEL * m + j];
-  if (!s.done) s = find_bucket<LEVEL>(hist + (size_t)j * kHistStride + hist_offset(LEVEL), s, fl);
+  LevelBins<LEVEL> bins;
+  bins.load(hist + (size_t)j * kHistStride + hist_offset(LEVEL));
+  if (!s.done) s = find_bucket<LEVEL>(bins, s, fl);
   if (threadIdx.x == 0) st[(size_t)(LEVEL + 1) * m + j] = s;
 }
 
