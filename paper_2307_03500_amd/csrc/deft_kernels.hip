@@ -404,15 +404,23 @@ __host__ __device__ inline uint32_t chunks_of(uint32_t start, uint32_t size, uin
   return (uint32_t)(((uint64_t)start + size - a + chunk_elems - 1) / chunk_elems);
 }
 
-// Histogram storage of one segment: level 0, 1, 2 one after the other.
-constexpr int kHistStride = (1 << kBits0) + (1 << kBits1) + (1 << kBits2);
+// Histogram storage of one segment: level 0, 1, 2 one after the other.  Level 0 is kept in
+// kRep0 copies -- workgroup b merges into copy b % kRep0, the bucket search adds them up --
+// because device-scope atomics on one address serialise (about 22 ns each) and the level-0
+// merge sends one per workgroup and occupied bin: the tail of the first pass.
+#ifndef DEFT_HIST0_COPIES
+#define DEFT_HIST0_COPIES 4
+#endif
+constexpr int kRep0 = DEFT_HIST0_COPIES;
+constexpr int kHistStride = (1 << kBits0) * kRep0 + (1 << kBits1) + (1 << kBits2);
 __host__ __device__ constexpr int hist_offset(int level) {
-  return level == 0 ? 0 : (level == 1 ? (1 << kBits0) : (1 << kBits0) + (1 << kBits1));
+  return level == 0 ? 0 : (level == 1 ? (1 << kBits0) * kRep0 : (1 << kBits0) * kRep0 + (1 << kBits1));
 }
 
 // Run by one whole workgroup: from the finished histogram of level LEVEL (its bins already
-// loaded, each thread its own) and the state `s` before that level, locate the bucket holding the k_rem-th largest key of the current
-// prefix and return the state after the level (in every thread).  If the bucket is taken
+// loaded, each thread its own) and the state `s` before that level, locate the bucket holding
+// the k_rem-th largest key of the current prefix and return the state after the level (in
+// every thread).  If the bucket is taken
 // entirely, or this was the last level, the threshold is resolved.
 // Bins of a level's histogram owned by a thread of the bucket search: thread t owns the kPer
 // bins just below kBins - t*kPer, i.e. threads walk the buckets from the largest keys down.
@@ -426,6 +434,13 @@ struct LevelBins {
     const int top = kBins - threadIdx.x * kPer;
 #pragma unroll
     for (int q = 0; q < kPer; ++q) v[q] = gh[top - 1 - q];
+    if (LEVEL == 0) {  // the other copies of the first level
+#pragma unroll
+      for (int c = 1; c < kRep0; ++c) {
+#pragma unroll
+        for (int q = 0; q < kPer; ++q) v[q] += gh[c * kBins + top - 1 - q];
+      }
+    }
   }
 };
 
@@ -548,7 +563,7 @@ __device__ __forceinline__ void hist0_chunk(const float* __restrict__ g, const S
     }
   }
   __syncthreads();
-  uint32_t* gh = hist + (size_t)j * kHistStride + hist_offset(0);
+  uint32_t* gh = hist + (size_t)j * kHistStride + hist_offset(0) + (blockIdx.x % kRep0) * kBins;
   int top_bin = 0;
   for (int b = threadIdx.x; b < kBins; b += kThreads) {
     const uint32_t v = lh[b];
@@ -617,7 +632,7 @@ __global__ __launch_bounds__(kThreads) void hist0_stream_kernel(
     const int j = seg_of_hchunk(seg, m, c);
     if (j != cur) {
       if (cur >= 0) {
-        uint32_t* gh = hist + (size_t)cur * kHistStride + hist_offset(0);
+        uint32_t* gh = hist + (size_t)cur * kHistStride + hist_offset(0) + (blockIdx.x % kRep0) * kBins;
         for (int b = threadIdx.x; b < kBins; b += kThreads) {
           const uint32_t v = lh[b];
           if (v) { atomicAdd(&gh[b], v); lh[b] = 0; }
@@ -656,7 +671,7 @@ __global__ __launch_bounds__(kThreads) void hist0_stream_kernel(
     c = draw[turn];
   }
   if (cur < 0) return;
-  uint32_t* gh = hist + (size_t)cur * kHistStride + hist_offset(0);
+  uint32_t* gh = hist + (size_t)cur * kHistStride + hist_offset(0) + (blockIdx.x % kRep0) * kBins;
   for (int b = threadIdx.x; b < kBins; b += kThreads) {
     const uint32_t v = lh[b];
     if (v) atomicAdd(&gh[b], v);
