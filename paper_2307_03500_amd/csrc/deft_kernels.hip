@@ -1252,30 +1252,37 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(
                              val_out, wtot);
     return;
   }
-  const bool on = threadIdx.x < n_live;
-  const uint2 e = on ? slots[(size_t)blockIdx.x * cap + threadIdx.x] : make_uint2(0u, 0u);
-  const uint32_t key = e.x & 0x7FFFFFFFu;
-  const bool is_eq = on && key == T;
-  bool take = on && key > T;
+  // entries in index order, kThreads at a time (one round unless the cap exceeds the workgroup)
   const unsigned long long below = (1ull << lane) - 1ull;
-  if (mode == 1) {
-    take = take || is_eq;
-  } else if (mode == 2) {
-    const unsigned long long eqb = __ballot(is_eq);
-    if (lane == 0) wtot[1][wave] = (uint32_t)__popcll(eqb);
+  uint32_t pos_base = ob, rank_base = eb;
+  for (uint32_t r0 = 0; r0 < n_live; r0 += kThreads) {
+    const bool on = r0 + threadIdx.x < n_live;
+    const uint2 e = on ? slots[(size_t)blockIdx.x * cap + r0 + threadIdx.x] : make_uint2(0u, 0u);
+    const uint32_t key = e.x & 0x7FFFFFFFu;
+    const bool is_eq = on && key == T;
+    bool take = on && key > T;
+    if (mode == 1) {
+      take = take || is_eq;
+    } else if (mode == 2) {
+      const unsigned long long eqb = __ballot(is_eq);
+      if (lane == 0) wtot[1][wave] = (uint32_t)__popcll(eqb);
+      __syncthreads();
+      uint32_t rank = rank_base + (uint32_t)__popcll(eqb & below);
+      for (int w = 0; w < wave; ++w) rank += wtot[1][w];
+      take = take || (is_eq && rank < r);
+      rank_base += wtot[1][0] + wtot[1][1] + wtot[1][2] + wtot[1][3];
+    }
+    const unsigned long long tb = __ballot(take);
+    if (lane == 0) wtot[0][wave] = (uint32_t)__popcll(tb);
     __syncthreads();
-    uint32_t rank = eb + (uint32_t)__popcll(eqb & below);
-    for (int w = 0; w < wave; ++w) rank += wtot[1][w];
-    take = take || (is_eq && rank < r);
-  }
-  const unsigned long long tb = __ballot(take);
-  if (lane == 0) wtot[0][wave] = (uint32_t)__popcll(tb);
-  __syncthreads();
-  uint32_t pos = ob + (uint32_t)__popcll(tb & below);
-  for (int w = 0; w < wave; ++w) pos += wtot[0][w];
-  if (take && pos < lim) {
-    idx_out[pos] = (int32_t)e.y;
-    val_out[pos] = __uint_as_float(e.x);
+    uint32_t pos = pos_base + (uint32_t)__popcll(tb & below);
+    for (int w = 0; w < wave; ++w) pos += wtot[0][w];
+    if (take && pos < lim) {
+      idx_out[pos] = (int32_t)e.y;
+      val_out[pos] = __uint_as_float(e.x);
+    }
+    pos_base += wtot[0][0] + wtot[0][1] + wtot[0][2] + wtot[0][3];
+    __syncthreads();  // wtot is rewritten in the next round
   }
 }
 
@@ -1403,8 +1410,10 @@ struct SelectLayout {
 // expected picks, 32..256): the conventional Top-k then overflowed in most chunks that hold
 // picks at all, because its picks sit in the few layers of large norm at many times the average
 // density.  The slot arrays are written sparsely, so the largest cap costs address space only.
-inline uint32_t slot_cap_for(uint64_t /*total_k*/, uint64_t /*share*/, uint32_t /*chunk_elems*/) {
-  return kMaxSlotCap;
+// Long vectors walk chunks twice as large and get twice the slots per chunk: the same address
+// space per element, and their slot kernels loop over the entries anyway.
+inline uint32_t slot_cap_for(uint64_t /*total_k*/, uint64_t /*share*/, uint32_t chunk_elems) {
+  return kMaxSlotCap * (chunk_elems / (kThreads * 4 * DEFT_SEL_ITERS_SMALL));
 }
 
 SelectLayout select_layout(int64_t m, uint64_t chunks, uint32_t cap = kMaxSlotCap) {
@@ -1530,7 +1539,7 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   for (const auto& d : segs) total_k += d.k;
   const uint32_t cap = slot_cap_for(total_k, (uint64_t)share, ce);
   // more than a quarter of a slot array per chunk expected on average
-  const bool dense = (double)ce * (double)total_k > 0.25 * kMaxSlotCap * (double)share;
+  const bool dense = (double)ce * (double)total_k > 0.25 * cap * (double)share;
   const bool inline_segs = pre && small && m <= kSegBatch && m <= pre->m_cap && chunks <= pre->chunks_cap;
   const SelectLayout w = inline_segs ? select_layout(pre->m_cap, pre->chunks_cap, cap) : select_layout(m, chunks, cap);
   if (w.total > ws_bytes) return DEFT_EWS;
