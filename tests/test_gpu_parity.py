@@ -341,6 +341,23 @@ def long_vector_shape():
     del os.environ["DEFT_LONG_VECTOR_ELEMS"]
 
 
+@pytest.mark.parametrize("frac", [20, 3])
+def test_topk_global_dense_on_one_long_segment(deft, long_vector_shape, frac):
+    """A dense conventional Top-k over a segment of more than 2048 long-shape chunks: the
+    workgroup-per-chunk ordered write with scanned chunk prefixes, from slot arrays holding more
+    entries than the workgroup has threads (K = N/20) and from the segment itself (K = N/3)."""
+    N = 2049 * 8192 + 123
+    rng = np.random.default_rng(77)
+    g = rng.standard_normal(N).astype(np.float32)
+    g[rng.integers(0, N, N // 50)] = 0.75  # a tie class that straddles the threshold region
+    sel = _selector(deft, [N], 1, 0.5)
+    K = N // frac
+    gi, gv = sel.topk_global(torch.from_numpy(g).to(DEV), K)
+    oi, ov = O.topk_global(g, K)
+    assert gi.tolist() == oi.tolist()
+    assert (_bits(gv) == _bits(ov)).all()
+
+
 @pytest.mark.parametrize("kind", ["normal", "all_equal", "few_levels", "signed_zero", "ascending"])
 def test_select_adversarial_values_long_vector_shape(deft, long_vector_shape, kind):
     test_select_adversarial_values(deft, kind)
