@@ -1,11 +1,14 @@
 #!/usr/bin/env python3
 """Benchmark of the DEFT selection path on one MI355X.
 
-A step is one worker's whole sparsifier call on a resident gradient vector:
-  norm pass over all N elements -> stream sync -> host plan (Alg. 3, Alg. 4) -> segmented
-  Top-k over the worker's layers (Alg. 5), outputs left in device memory.
+A step is one worker's whole sparsifier call on a resident gradient vector, made through the
+single entry point deft_sparsify:
+  norm pass over all N elements -> the host waits for the L sums (it polls the pinned array
+  they are written to) -> host plan (Alg. 3, Alg. 4) -> segmented Top-k over the worker's
+  layers (Alg. 5) enqueued, outputs left in device memory.
 Steps follow each other on one stream without a sync at the end of a step (the timed region
-is bracketed by synchronisations), as iterations of a training loop would.
+is bracketed by synchronisations), as iterations of a training loop would.  --stepwise times
+the separate C-ABI calls with a stream synchronisation after the norm pass instead.
 value = GB/s scanned = (4N + 4S_r + 8k_r) / t, the algorithmic bytes of the method (re-reads of
 a multi-pass select are not credited).  The conventional Top-k over the whole vector
 (comparison path, (4N + 8K)/t) is timed as a second leg and reported in the same line.

@@ -30,8 +30,10 @@
  *     magnitudes the lower index is selected first.  Selected entries are reported in
  *     ascending index order with their original bit pattern.
  *   - Results are deterministic: the same inputs give the same bits.
- *   - Environment: DEFT_LONG_VECTOR_ELEMS=<n> moves the element count above which the selection
- *     uses its long-vector launch shape (default 2^25).  It changes speed only, never results.
+ *   - The library reads no environment variable and has no settings of its own: what tunes a
+ *     call travels in its arguments.  The selection calls take a launch shape: DEFT_SHAPE_AUTO
+ *     picks by size (long-vector kernels above 2^25 selected-from elements); DEFT_SHAPE_SHORT and
+ *     DEFT_SHAPE_LONG force one.  The shape changes speed only, never results.
  */
 #ifndef DEFT_H
 #define DEFT_H
@@ -49,6 +51,10 @@ extern "C" {
 #define DEFT_EWS (-3)    /* workspace too small (see deft_workspace_bytes) */
 #define DEFT_ECAP (-4)   /* output capacity too small */
 #define DEFT_EHIP (-5)   /* HIP launch/runtime error */
+
+#define DEFT_SHAPE_AUTO 0
+#define DEFT_SHAPE_SHORT 1
+#define DEFT_SHAPE_LONG 2
 
 #define DEFT_OP_NORMS 0
 #define DEFT_OP_SELECT 1
@@ -93,6 +99,13 @@ int deft_check_layout(const int64_t* offsets_host, int32_t L, int64_t N);
  */
 int deft_layer_norms(const float* g_dev, int64_t N, const int64_t* offsets_dev, int32_t L,
                      double* sumsq_dev, void* ws_dev, size_t ws_bytes, void* stream);
+
+/*
+ * First statement of Alg. 3 (k = n_g * d; density is defined in the footnote of Sec. 1):
+ * K = floor(N * d + 0.5) in fp64, the number of entries the sparsifier selects in total.
+ * Errors: DEFT_EINVAL (null, N < 1, d outside (0,1]), DEFT_ERANGE (N >= 2^31).
+ */
+int deft_total_k(int64_t N, double d, int64_t* K_out);
 
 /*
  * norms[l] = sqrt(sumsq[l]) on the host (IEEE correctly-rounded square root): the step between
@@ -155,13 +168,14 @@ int deft_cost_model(const int64_t* sizes, const int64_t* k, const int32_t* owner
  *   out_cap            in   capacity of idx/val in entries; must be >= sum of the k's
  *   ws_dev             scratch, deft_workspace_bytes(DEFT_OP_SELECT, share, my_count) bytes
  *                      where share >= total size of the caller's layers; 16-byte aligned
+ *   launch_shape       in   DEFT_SHAPE_AUTO, _SHORT or _LONG
  * my_count == 0 is valid and enqueues nothing.
  * Errors: DEFT_EINVAL, DEFT_ERANGE, DEFT_EWS, DEFT_ECAP, DEFT_EHIP.
  */
 int deft_select(const float* g_dev, int64_t N, const int64_t* offsets_host, const int64_t* k_host,
                 int32_t L, const int32_t* my_layers_host, int32_t my_count, int32_t* idx_out_dev,
                 float* val_out_dev, int64_t* seg_off_host, int64_t out_cap, void* ws_dev,
-                size_t ws_bytes, void* stream);
+                size_t ws_bytes, int32_t launch_shape, void* stream);
 
 /*
  * Conventional Top-k sparsifier (Sec. 1; the n = 1 case of Sec. 5.4): the K entries of largest
@@ -170,7 +184,24 @@ int deft_select(const float* g_dev, int64_t N, const int64_t* offsets_host, cons
  * Errors: DEFT_EINVAL, DEFT_ERANGE, DEFT_EWS, DEFT_EHIP.
  */
 int topk_global(const float* g_dev, int64_t N, int64_t K, int32_t* idx_out_dev,
-                float* val_out_dev, void* ws_dev, size_t ws_bytes, void* stream);
+                float* val_out_dev, void* ws_dev, size_t ws_bytes, int32_t launch_shape,
+                void* stream);
+
+/*
+ * Cyclic local Top-k, the comparison scheme of Sec. 1 and Sec. 3.1: in iteration t the worker
+ * t mod n_workers (deft_cltk_leader) selects the conventional Top-k of its own vector, with
+ * K = deft_total_k(N, d), for everyone; the other workers select nothing.
+ *   count_out  out  K on the leader (idx/val hold K entries once the stream is synchronised),
+ *                   0 on every other rank (nothing enqueued, nothing written)
+ *   out_cap    in   capacity of idx/val in entries; the leader needs out_cap >= K
+ * Other arguments as topk_global.  Errors: those of topk_global; DEFT_EINVAL also for rank outside
+ * [0, n_workers), n_workers < 1, iteration < 0, d outside (0,1]; DEFT_ECAP.
+ */
+int deft_cltk_leader(int64_t iteration, int32_t n_workers, int32_t* leader_out);
+int deft_cltk_select(const float* g_dev, int64_t N, double d, int32_t n_workers, int32_t rank,
+                     int64_t iteration, int32_t* idx_out_dev, float* val_out_dev, int64_t out_cap,
+                     void* ws_dev, size_t ws_bytes, int32_t launch_shape, void* stream,
+                     int64_t* count_out);
 
 /*
  * Alg. 1, the step before the sparsifier, fused with the norm pass of Sec. 4.2:
@@ -210,12 +241,14 @@ int deft_gather_zero(float* acc_dev, int64_t N, const int32_t* idx_dev, int64_t 
  * delivered its sums (the host plan needs them) and returns with the selection enqueued on
  * `stream`; idx/val are valid once the caller has synchronised the stream.  It waits by
  * reading job->sumsq_pinned (every entry is set to an impossible bit pattern before the norm
- * pass is enqueued and overwritten by it); after DEFT_SPIN_US microseconds (environment,
- * default 20000; 0 = at once) it falls back to hipStreamSynchronize.  Not capturable in a HIP
- * graph (it waits on the host).
+ * pass is enqueued and overwritten by it); after job->spin_us microseconds it falls back to
+ * hipStreamSynchronize.  Not capturable in a HIP graph (it waits on the host).
  *
  * deft_job holds what stays the same from call to call; the caller fills it once.
  *   N, L, n_workers, rank, d     the job (d in (0,1], rank in [0, n_workers))
+ *   launch_shape                 DEFT_SHAPE_AUTO, _SHORT or _LONG, as for deft_select
+ *   spin_us                      how long to poll for the sums before blocking in the stream
+ *                                synchronisation: 0 = default (20000), negative = do not poll
  *   offsets_host / offsets_dev   the same L+1 offsets in host and in device memory
  *   sizes_host[L]                layer sizes (offsets[l+1] - offsets[l])
  *   sumsq_pinned[L]              pinned host memory the device can write (hipHostMalloc);
@@ -242,7 +275,7 @@ typedef struct deft_job {
   int32_t L;
   int32_t n_workers;
   int32_t rank;
-  int32_t reserved; /* 0 */
+  int32_t launch_shape;
   double d;
   const int64_t* offsets_host;
   const int64_t* offsets_dev;
@@ -258,6 +291,7 @@ typedef struct deft_job {
   int64_t out_cap;
   void* ws_dev;
   size_t ws_bytes;
+  int64_t spin_us;
 } deft_job;
 
 int deft_sparsify(const deft_job* job, const float* g_dev, int64_t iteration, void* stream,

@@ -54,34 +54,25 @@ def partition(tensor_sizes: Sequence[int], n_workers: int) -> Tuple[List[int], L
     """
     if n_workers < 1:
         raise ValueError("n_workers must be >= 1")
-    n_g = sum(int(s) for s in tensor_sizes)
-    offsets = [0]
-    layer_tensor: List[int] = []
-    alloc_pos = 0
-    for t, size in enumerate(tensor_sizes):
-        size = int(size)
-        if size < 0:
-            raise ValueError("negative tensor size")
-        # tensor.size > n_g / n_workers, evaluated exactly in integers
+    sizes = [int(s) for s in tensor_sizes]
+    if any(s < 0 for s in sizes):
+        raise ValueError("negative tensor size")
+    n_g = sum(sizes)
+    # the pieces every tensor contributes, in model order
+    pieces: List[Tuple[int, int]] = []  # (tensor index, piece size)
+    for t, size in enumerate(sizes):
+        # "larger than n_g / n_workers", decided exactly in integers
         if size * n_workers > n_g:
-            quotient, remainder = divmod(size, n_workers)
-            for _ in range(n_workers):
-                size_layer = quotient
-                if remainder > 0:
-                    size_layer += 1
-                    remainder -= 1
-                if size_layer == 0:
-                    continue
-                alloc_pos += size_layer
-                offsets.append(alloc_pos)
-                layer_tensor.append(t)
+            small, extra = divmod(size, n_workers)
+            # `extra` pieces of small + 1 elements come first, then pieces of `small`
+            cut = [small + 1] * extra + [small] * (n_workers - extra)
         else:
-            if size == 0:
-                continue
-            alloc_pos += size
-            offsets.append(alloc_pos)
-            layer_tensor.append(t)
-    return offsets, layer_tensor
+            cut = [size]
+        pieces.extend((t, c) for c in cut if c > 0)
+    offsets = [0]
+    for _, c in pieces:
+        offsets.append(offsets[-1] + c)
+    return offsets, [t for t, _ in pieces]
 
 
 # --------------------------------------------------------------------------------------
@@ -172,23 +163,24 @@ def assign_layers(sizes: Sequence[int], k: Sequence[int], n_workers: int, iterat
     if n_workers < 1 or not (0 <= rank < n_workers) or iteration < 0:
         raise ValueError("bad n_workers / rank / iteration")
     L = len(sizes)
-    cycle = iteration % n_workers
-    curr_part = (cycle + rank) % n_workers
-    size_bin = [0.0] * n_workers
-    alloc_bin: List[List[int]] = [[] for _ in range(n_workers)]
     cost = layer_costs(sizes, k)
-    for _ in range(L):
-        val_max = max(cost)
-        idx_max = cost.index(val_max)
-        bin_min = size_bin.index(min(size_bin))
-        alloc_bin[bin_min].append(idx_max)
-        size_bin[bin_min] = size_bin[bin_min] + val_max
-        cost[idx_max] = -1.0
+    load = [0.0] * n_workers                      # summed cost of each bin so far
+    alloc_bin: List[List[int]] = [[] for _ in range(n_workers)]
+    unplaced = list(range(L))
+    while unplaced:
+        # most expensive layer still unplaced; among equals the one that comes first
+        layer = max(unplaced, key=lambda l: (cost[l], -l))
+        # lightest bin; among equals the lowest id
+        target = min(range(n_workers), key=lambda b: (load[b], b))
+        alloc_bin[target].append(layer)
+        load[target] = load[target] + cost[layer]
+        unplaced.remove(layer)
     owner_bin = [0] * L
-    for b, lst in enumerate(alloc_bin):
-        for l in lst:
+    for b, members in enumerate(alloc_bin):
+        for l in members:
             owner_bin[l] = b
-    return owner_bin, list(alloc_bin[curr_part]), alloc_bin
+    mine = (iteration % n_workers + rank) % n_workers
+    return owner_bin, list(alloc_bin[mine]), alloc_bin
 
 
 # --------------------------------------------------------------------------------------

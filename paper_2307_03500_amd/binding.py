@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdeft.so"
 
 DEFT_OK, DEFT_EINVAL, DEFT_ERANGE, DEFT_EWS, DEFT_ECAP, DEFT_EHIP = 0, -1, -2, -3, -4, -5
 OP_NORMS, OP_SELECT, OP_TOPK_GLOBAL = 0, 1, 2
+SHAPE_AUTO, SHAPE_SHORT, SHAPE_LONG = 0, 1, 2
 
 # Every pointer travels as a plain address (void*): numpy arrays pass `arr.ctypes.data`,
 # torch tensors pass `t.data_ptr()`; callers on a hot path cache those integers.
@@ -27,6 +28,10 @@ SIGNATURES = {
     "deft_check_layout": (C.c_int, [_P, C.c_int32, C.c_int64]),
     "deft_layer_norms": (C.c_int, [_P, C.c_int64, _P, C.c_int32, _P, _P, C.c_size_t, _P]),
     "deft_norms_from_sumsq": (C.c_int, [_P, C.c_int32, _P]),
+    "deft_total_k": (C.c_int, [C.c_int64, C.c_double, _P]),
+    "deft_cltk_leader": (C.c_int, [C.c_int64, C.c_int32, _P]),
+    "deft_cltk_select": (C.c_int, [_P, C.c_int64, C.c_double, C.c_int32, C.c_int32, C.c_int64, _P, _P,
+                                   C.c_int64, _P, C.c_size_t, C.c_int32, _P, _P]),
     "deft_accumulate_norms": (C.c_int, [_P, _P, C.c_float, _P, C.c_int64, _P, C.c_int32, _P, _P,
                                         C.c_size_t, _P]),
     "deft_gather_zero": (C.c_int, [_P, C.c_int64, _P, C.c_int64, _P, _P]),
@@ -34,8 +39,8 @@ SIGNATURES = {
     "deft_assign_layers": (C.c_int, [_P, _P, C.c_int32, C.c_int32, C.c_int64, C.c_int32, _P, _P, _P]),
     "deft_cost_model": (C.c_int, [_P, _P, _P, C.c_int32, C.c_int32, C.c_int64, C.c_int64, _P, _P]),
     "deft_select": (C.c_int, [_P, C.c_int64, _P, _P, C.c_int32, _P, C.c_int32, _P, _P, _P,
-                              C.c_int64, _P, C.c_size_t, _P]),
-    "topk_global": (C.c_int, [_P, C.c_int64, C.c_int64, _P, _P, _P, C.c_size_t, _P]),
+                              C.c_int64, _P, C.c_size_t, C.c_int32, _P]),
+    "topk_global": (C.c_int, [_P, C.c_int64, C.c_int64, _P, _P, _P, C.c_size_t, C.c_int32, _P]),
     "deft_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int64, C.c_int32]),
     "deft_sparsify": (C.c_int, [_P, _P, C.c_int64, _P, _P, _P, _P]),
     "deft_accumulate_sparsify": (C.c_int, [_P, _P, _P, C.c_float, _P, C.c_int64, _P, _P, _P, _P]),
@@ -47,11 +52,12 @@ _lib = None
 class DeftJob(C.Structure):
     """struct deft_job of deft.h (the per-job arguments of deft_sparsify), field for field."""
     _fields_ = [("N", C.c_int64), ("L", C.c_int32), ("n_workers", C.c_int32), ("rank", C.c_int32),
-                ("reserved", C.c_int32), ("d", C.c_double), ("offsets_host", _P),
+                ("launch_shape", C.c_int32), ("d", C.c_double), ("offsets_host", _P),
                 ("offsets_dev", _P), ("sizes_host", _P), ("sumsq_pinned", _P), ("norms_host", _P),
                 ("k_host", _P), ("owner_bin_host", _P), ("my_layers_host", _P),
                 ("seg_off_host", _P), ("idx_out_dev", _P), ("val_out_dev", _P),
-                ("out_cap", C.c_int64), ("ws_dev", _P), ("ws_bytes", C.c_size_t)]
+                ("out_cap", C.c_int64), ("ws_dev", _P), ("ws_bytes", C.c_size_t),
+                ("spin_us", C.c_int64)]
 
 
 class DeftError(RuntimeError):
@@ -115,6 +121,19 @@ def deft_partition(tensor_sizes: Sequence[int], n_workers: int) -> Tuple[np.ndar
 def deft_check_layout(offsets, N: int) -> int:
     off = _i64(offsets)
     return lib().deft_check_layout(_p(off), len(off) - 1, int(N))
+
+
+def deft_total_k(N: int, d: float) -> int:
+    K = C.c_int64(0)
+    _check(lib().deft_total_k(int(N), float(d), C.addressof(K)), "deft_total_k")
+    return int(K.value)
+
+
+def deft_cltk_leader(iteration: int, n_workers: int) -> int:
+    leader = C.c_int32(0)
+    _check(lib().deft_cltk_leader(int(iteration), int(n_workers), C.addressof(leader)),
+           "deft_cltk_leader")
+    return int(leader.value)
 
 
 def deft_norms_from_sumsq(sumsq) -> np.ndarray:
@@ -187,7 +206,8 @@ def deft_gather_zero(acc, idx, vals_out, stream=None) -> None:
                                   vals_out.data_ptr(), _stream(stream)), "deft_gather_zero")
 
 
-def deft_select(g, offsets_host, k_host, my_layers_host, idx_out, val_out, ws, stream=None) -> np.ndarray:
+def deft_select(g, offsets_host, k_host, my_layers_host, idx_out, val_out, ws, stream=None,
+                shape: int = SHAPE_AUTO) -> np.ndarray:
     """Enqueues Alg. 5 for the given layers; returns seg_off (host, int64, len my_count+1)."""
     off, kk, mine = _i64(offsets_host), _i64(k_host), _i32(my_layers_host)
     seg = np.zeros(len(mine) + 1, np.int64)
@@ -195,15 +215,29 @@ def deft_select(g, offsets_host, k_host, my_layers_host, idx_out, val_out, ws, s
                              len(off) - 1, _p(mine), len(mine),
                              idx_out.data_ptr(), val_out.data_ptr(),
                              _p(seg), idx_out.numel(), ws.data_ptr(),
-                             ws.numel() * ws.element_size(), _stream(stream)), "deft_select")
+                             ws.numel() * ws.element_size(), int(shape), _stream(stream)),
+           "deft_select")
     return seg
 
 
-def topk_global(g, K: int, idx_out, val_out, ws, stream=None) -> None:
+def topk_global(g, K: int, idx_out, val_out, ws, stream=None, shape: int = SHAPE_AUTO) -> None:
     _check(lib().topk_global(g.data_ptr(), g.numel(), int(K),
                              idx_out.data_ptr(), val_out.data_ptr(),
-                             ws.data_ptr(), ws.numel() * ws.element_size(),
+                             ws.data_ptr(), ws.numel() * ws.element_size(), int(shape),
                              _stream(stream)), "topk_global")
+
+
+def deft_cltk_select(g, d: float, n_workers: int, rank: int, iteration: int, idx_out, val_out, ws,
+                     stream=None, shape: int = SHAPE_AUTO) -> int:
+    """Cyclic local Top-k: enqueues the conventional Top-k on the iteration's leader only;
+    returns the number of entries this rank selected (K or 0)."""
+    cnt = C.c_int64(0)
+    _check(lib().deft_cltk_select(g.data_ptr(), g.numel(), float(d), int(n_workers), int(rank),
+                                  int(iteration), idx_out.data_ptr(), val_out.data_ptr(),
+                                  idx_out.numel(), ws.data_ptr(), ws.numel() * ws.element_size(),
+                                  int(shape), _stream(stream), C.addressof(cnt)),
+           "deft_cltk_select")
+    return int(cnt.value)
 
 
 def deft_sparsify(job: DeftJob, g, iteration: int, stream=None, norms_done_event: int = 0):

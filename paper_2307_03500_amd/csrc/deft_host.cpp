@@ -26,8 +26,16 @@ extern "C" const char* deft_strerror(int status) {
   }
 }
 
-// Alg. 2.  The test "tensor.size > n_g / n_workers" is evaluated as size * n > n_g, which is
-// the same predicate for integer sizes whether the quotient is taken as real or integer.
+// Alg. 2 (Sec. 4.1).  A tensor is cut when it holds more than n_g / n_workers elements; for
+// integer sizes that is the predicate size * n_workers > n_g whether the quotient is taken as
+// real or integer.  Fraction i of a cut tensor of s = q * n + r elements (0 <= r < n) is the
+// half-open range [i*q + min(i, r), (i+1)*q + min(i+1, r)) of the tensor: the first r fractions
+// hold q + 1 elements, the others q, and together they tile the tensor.  Ranges that come out
+// empty (s < n) produce no layer.
+namespace {
+inline int64_t fraction_begin(int64_t q, int64_t r, int64_t i) { return i * q + std::min(i, r); }
+}  // namespace
+
 extern "C" int deft_partition(const int64_t* tensor_sizes, int32_t T, int32_t n_workers,
                               int64_t* offsets, int32_t* layer_tensor, int32_t cap,
                               int32_t* L_out) {
@@ -38,37 +46,27 @@ extern "C" int deft_partition(const int64_t* tensor_sizes, int32_t T, int32_t n_
     n_g += tensor_sizes[t];
     if (n_g > kMaxN) return DEFT_ERANGE;
   }
-  // first sweep: count layers so that nothing is written when the capacity is short
+  const int64_t n = n_workers;
+  // layers each tensor contributes: 0 (empty), 1 (kept whole) or min(s, n) (cut)
   int64_t need = 0;
   for (int32_t t = 0; t < T; ++t) {
     const int64_t s = tensor_sizes[t];
-    if (s == 0) continue;
-    if (s * n_workers > n_g) need += std::min<int64_t>(s, n_workers);
-    else need += 1;
+    need += s == 0 ? 0 : (s * n > n_g ? std::min(s, n) : 1);
   }
-  if (need > cap) return DEFT_ECAP;
+  if (need > cap) return DEFT_ECAP;  // nothing written
   int32_t L = 0;
-  int64_t alloc_pos = 0;
+  int64_t base = 0;  // first element of tensor t in the flat vector
   offsets[0] = 0;
-  auto emit = [&](int64_t size_layer, int32_t t) {
-    alloc_pos += size_layer;
-    if (layer_tensor) layer_tensor[L] = t;
-    offsets[++L] = alloc_pos;
-  };
   for (int32_t t = 0; t < T; ++t) {
     const int64_t s = tensor_sizes[t];
-    if (s == 0) continue;
-    if (s * n_workers > n_g) {
-      const int64_t quotient = s / n_workers;
-      int64_t remainder = s % n_workers;
-      for (int32_t i = 0; i < n_workers; ++i) {
-        int64_t size_layer = quotient;
-        if (remainder > 0) { size_layer += 1; remainder -= 1; }
-        if (size_layer > 0) emit(size_layer, t);
-      }
-    } else {
-      emit(s, t);
+    const bool cut = s * n > n_g;
+    const int64_t parts = s == 0 ? 0 : (cut ? std::min(s, n) : 1);
+    const int64_t q = cut ? s / n : s, r = cut ? s % n : 0;
+    for (int64_t i = 0; i < parts; ++i) {
+      if (layer_tensor) layer_tensor[L] = t;
+      offsets[++L] = base + fraction_begin(q, r, i + 1);
     }
+    base += s;
   }
   *L_out = L;
   return DEFT_OK;
@@ -99,6 +97,22 @@ void sort_descending(const double* v, int32_t L, std::vector<SortKey>& out) {
   std::sort(out.begin(), out.end());
 }
 }  // namespace
+
+// First statement of Alg. 3 (k = n_g * d; density as defined in the footnote of Sec. 1), made an
+// integer by rounding half up in fp64.
+extern "C" int deft_total_k(int64_t N, double d, int64_t* K_out) {
+  if (!K_out || N < 1 || N > kMaxN) return N > kMaxN ? DEFT_ERANGE : DEFT_EINVAL;
+  if (!(d > 0.0) || !(d <= 1.0)) return DEFT_EINVAL;
+  *K_out = (int64_t)std::floor((double)N * d + 0.5);
+  return DEFT_OK;
+}
+
+// Cyclic local Top-k (Sec. 1; Sec. 3.1): workers take turns, one per iteration.
+extern "C" int deft_cltk_leader(int64_t iteration, int32_t n_workers, int32_t* leader_out) {
+  if (!leader_out || n_workers < 1 || iteration < 0) return DEFT_EINVAL;
+  *leader_out = (int32_t)(iteration % n_workers);
+  return DEFT_OK;
+}
 
 extern "C" int deft_norms_from_sumsq(const double* sumsq, int32_t L, double* norms) {
   if (!sumsq || !norms || L < 1) return DEFT_EINVAL;
@@ -133,7 +147,9 @@ extern "C" int deft_alloc_k(const double* norms, const int64_t* sizes, int32_t L
     acc = norms[order[j]] + acc;
     norm_remain[j] = acc;
   }
-  int64_t k_remain = (int64_t)std::floor((double)N * d + 0.5);
+  int64_t k_remain = 0;
+  const int rc = deft_total_k(N, d, &k_remain);
+  if (rc != DEFT_OK) return rc;
   for (int32_t j = 0; j < L; ++j) {
     const int32_t l = order[j];
     double k_temp = 0.0;
@@ -168,8 +184,8 @@ extern "C" int deft_assign_layers(const int64_t* sizes, const int64_t* k, int32_
   if (!sizes || !k || !owner_bin || !my_layers || !my_count) return DEFT_EINVAL;
   if (L < 1 || n_workers < 1 || rank < 0 || rank >= n_workers || iteration < 0) return DEFT_EINVAL;
   if (!check_sizes_k(sizes, k, L)) return DEFT_EINVAL;
-  const int32_t cycle = (int32_t)(iteration % n_workers);
-  const int32_t curr_part = (cycle + rank) % n_workers;
+  // the bin -> worker map turns by one place per iteration
+  const int32_t my_bin = (int32_t)((iteration % n_workers + rank) % n_workers);
   // layers in (cost descending, position ascending) order
   thread_local std::vector<double> cost;
   thread_local std::vector<SortKey> item;
@@ -186,11 +202,11 @@ extern "C" int deft_assign_layers(const int64_t* sizes, const int64_t* k, int32_
   };
   int32_t cnt = 0;
   for (int32_t j = 0; j < L; ++j) {
-    const int32_t idx_max = (int32_t)(uint32_t)item[j];
-    const int32_t bin_min = heap[0].second;
-    owner_bin[idx_max] = bin_min;
-    if (bin_min == curr_part) my_layers[cnt++] = idx_max;
-    heap[0].first = heap[0].first + cost[idx_max];
+    const int32_t layer = (int32_t)(uint32_t)item[j];  // costliest layer not yet placed
+    const int32_t lightest = heap[0].second;
+    owner_bin[layer] = lightest;
+    if (lightest == my_bin) my_layers[cnt++] = layer;
+    heap[0].first = heap[0].first + cost[layer];
     // sift the grown bin down
     int32_t i = 0;
     for (;;) {

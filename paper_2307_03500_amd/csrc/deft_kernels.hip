@@ -29,7 +29,6 @@
 #include <algorithm>
 #include <atomic>
 #include <chrono>
-#include <cstdlib>
 #include <cstring>
 #include <vector>
 
@@ -1387,19 +1386,12 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 #define DEFT_SEL_ITERS_LARGE 8
 #endif
 // Vectors above this many elements use the long-vector launch shape (larger chunks, separate
-// bucket-search kernels, wave-per-chunk slot kernels).  DEFT_LONG_VECTOR_ELEMS in the
-// environment overrides the threshold (for tests and tuning; read at every call).
+// bucket-search kernels, wave-per-chunk slot kernels) unless the caller names a shape.
 constexpr int64_t kLongVectorElems = int64_t(1) << 25;
-inline int64_t long_vector_elems() {
-  const char* e = std::getenv("DEFT_LONG_VECTOR_ELEMS");
-  if (e && *e) {
-    const long long v = std::atoll(e);
-    if (v >= 0) return (int64_t)v;
-  }
-  return kLongVectorElems;
-}
-inline int chunk_iters_for(int64_t elems) {
-  return elems > long_vector_elems() ? DEFT_SEL_ITERS_LARGE : DEFT_SEL_ITERS_SMALL;
+inline bool valid_shape(int32_t shape) { return shape >= DEFT_SHAPE_AUTO && shape <= DEFT_SHAPE_LONG; }
+inline int chunk_iters_for(int64_t elems, int32_t shape) {
+  const bool lng = shape == DEFT_SHAPE_LONG || (shape == DEFT_SHAPE_AUTO && elems > kLongVectorElems);
+  return lng ? DEFT_SEL_ITERS_LARGE : DEFT_SEL_ITERS_SMALL;
 }
 
 struct SelectLayout {
@@ -1513,11 +1505,11 @@ inline size_t clear_words(const SelectLayout& w) { return (w.cgt - w.hist) / siz
 // selections of at most kSegBatch segments skip the set-up launch: the descriptors travel with
 // the first pass.
 int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t share,
-               int32_t* idx_out, float* val_out, void* ws, size_t ws_bytes, hipStream_t s,
-               const Precleared* pre = nullptr) {
+               int32_t* idx_out, float* val_out, void* ws, size_t ws_bytes, int32_t shape,
+               hipStream_t s, const Precleared* pre = nullptr) {
   const int m = (int)segs_in.size();
   if (m == 0) return DEFT_OK;
-  const int iters = chunk_iters_for(share);
+  const int iters = chunk_iters_for(share, shape);
   const bool small = iters == DEFT_SEL_ITERS_SMALL;
   const uint32_t ce = (uint32_t)kThreads * 4 * iters;
   const uint32_t hce = 4 * ce;
@@ -1666,8 +1658,9 @@ namespace {
 int select_layers(const float* g_dev, int64_t N, const int64_t* offsets_host, const int64_t* k_host,
                   int32_t L, const int32_t* my_layers_host, int32_t my_count, int32_t* idx_out_dev,
                   float* val_out_dev, int64_t* seg_off_host, int64_t out_cap, void* ws_dev,
-                  size_t ws_bytes, void* stream, const Precleared* pre) {
-  if (!g_dev || !offsets_host || !k_host || !seg_off_host || my_count < 0 || out_cap < 0)
+                  size_t ws_bytes, int32_t shape, void* stream, const Precleared* pre) {
+  if (!g_dev || !offsets_host || !k_host || !seg_off_host || my_count < 0 || out_cap < 0 ||
+      !valid_shape(shape))
     return DEFT_EINVAL;
   if (my_count > 0 && !my_layers_host) return DEFT_EINVAL;
   const int lay = deft_check_layout(offsets_host, L, N);
@@ -1705,7 +1698,7 @@ int select_layers(const float* g_dev, int64_t N, const int64_t* offsets_host, co
     if (share > kMaxN) return DEFT_ERANGE;  // a layer listed more than once
     if (ws_bytes < deft_workspace_bytes(DEFT_OP_SELECT, share, (int32_t)segs.size())) return DEFT_EWS;
   }
-  const int rc = run_select(g_dev, segs, share, idx_out_dev, val_out_dev, ws_dev, ws_bytes,
+  const int rc = run_select(g_dev, segs, share, idx_out_dev, val_out_dev, ws_dev, ws_bytes, shape,
                             static_cast<hipStream_t>(stream), pre);
   if (rc != DEFT_OK) return rc;
   std::copy(seg_off.begin(), seg_off.end(), seg_off_host);
@@ -1717,14 +1710,16 @@ extern "C" int deft_select(const float* g_dev, int64_t N, const int64_t* offsets
                            const int64_t* k_host, int32_t L, const int32_t* my_layers_host,
                            int32_t my_count, int32_t* idx_out_dev, float* val_out_dev,
                            int64_t* seg_off_host, int64_t out_cap, void* ws_dev, size_t ws_bytes,
-                           void* stream) {
+                           int32_t launch_shape, void* stream) {
   return select_layers(g_dev, N, offsets_host, k_host, L, my_layers_host, my_count, idx_out_dev,
-                       val_out_dev, seg_off_host, out_cap, ws_dev, ws_bytes, stream, nullptr);
+                       val_out_dev, seg_off_host, out_cap, ws_dev, ws_bytes, launch_shape, stream,
+                       nullptr);
 }
 
 extern "C" int topk_global(const float* g_dev, int64_t N, int64_t K, int32_t* idx_out_dev,
-                           float* val_out_dev, void* ws_dev, size_t ws_bytes, void* stream) {
-  if (!g_dev || N < 1 || K < 0 || K > N) return DEFT_EINVAL;
+                           float* val_out_dev, void* ws_dev, size_t ws_bytes, int32_t launch_shape,
+                           void* stream) {
+  if (!g_dev || N < 1 || K < 0 || K > N || !valid_shape(launch_shape)) return DEFT_EINVAL;
   if (N > kMaxN) return DEFT_ERANGE;
   if (reinterpret_cast<uintptr_t>(g_dev) & 15u) return DEFT_EINVAL;
   if (K == 0) return DEFT_OK;
@@ -1738,8 +1733,30 @@ extern "C" int topk_global(const float* g_dev, int64_t N, int64_t K, int32_t* id
   segs[0].out_off = 0;
   segs[0].chunk_base = 0;
   segs[0].hchunk_base = 0;
-  return run_select(g_dev, segs, N, idx_out_dev, val_out_dev, ws_dev, ws_bytes,
+  return run_select(g_dev, segs, N, idx_out_dev, val_out_dev, ws_dev, ws_bytes, launch_shape,
                     static_cast<hipStream_t>(stream));
+}
+
+// Cyclic local Top-k (Sec. 1; Sec. 3.1): the worker whose turn it is selects the conventional
+// Top-k of its own vector; the others select nothing.
+extern "C" int deft_cltk_select(const float* g_dev, int64_t N, double d, int32_t n_workers,
+                                int32_t rank, int64_t iteration, int32_t* idx_out_dev,
+                                float* val_out_dev, int64_t out_cap, void* ws_dev, size_t ws_bytes,
+                                int32_t launch_shape, void* stream, int64_t* count_out) {
+  if (!count_out || rank < 0 || rank >= n_workers || out_cap < 0) return DEFT_EINVAL;
+  int32_t leader = 0;
+  int64_t K = 0;
+  int rc = deft_cltk_leader(iteration, n_workers, &leader);
+  if (rc == DEFT_OK) rc = deft_total_k(N, d, &K);
+  if (rc != DEFT_OK) return rc;
+  if (rank != leader) {
+    *count_out = 0;
+    return DEFT_OK;
+  }
+  if (K > out_cap) return DEFT_ECAP;
+  rc = topk_global(g_dev, N, K, idx_out_dev, val_out_dev, ws_dev, ws_bytes, launch_shape, stream);
+  if (rc == DEFT_OK) *count_out = K;
+  return rc;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1750,20 +1767,17 @@ namespace {
 // bits clear, and the default NaN is 0x7ff8000000000000.
 constexpr uint64_t kSumUnset = ~uint64_t(0);
 
-// Read on every call so that a caller (or a test) can change it while the process runs.
-int64_t spin_limit_us() {
-  const char* e = std::getenv("DEFT_SPIN_US");
-  if (!e || !*e) return 20000;
-  const long long x = std::atoll(e);
-  return int64_t(x < 0 ? 0 : x);
+// How long deft_sparsify polls before it blocks, from the job: 0 = the default.
+constexpr int64_t kDefaultSpinUs = 20000;
+inline int64_t spin_limit_us(const deft_job& j) {
+  return j.spin_us == 0 ? kDefaultSpinUs : (j.spin_us < 0 ? 0 : j.spin_us);
 }
 
 // Waits until the norm pass has overwritten every armed entry.  Polls the pinned array for at
-// most spin_limit_us(), then blocks in hipStreamSynchronize.
-int await_sums(const double* sumsq_pinned, int32_t L, hipStream_t s) {
+// most `limit` microseconds, then blocks in hipStreamSynchronize.
+int await_sums(const double* sumsq_pinned, int32_t L, hipStream_t s, int64_t limit) {
   const volatile uint64_t* w = reinterpret_cast<const volatile uint64_t*>(sumsq_pinned);
   int32_t cur = 0;
-  const int64_t limit = spin_limit_us();
   if (limit > 0) {
     const auto t0 = std::chrono::steady_clock::now();
     uint32_t spins = 0;
@@ -1803,7 +1817,7 @@ int sparsify(const deft_job* job, const float* src, const float* grad, float eta
       !j.k_host || !j.owner_bin_host || !j.my_layers_host || !j.seg_off_host || !j.ws_dev)
     return DEFT_EINVAL;
   if (j.n_workers < 1 || j.rank < 0 || j.rank >= j.n_workers || iteration < 0 ||
-      !(j.d > 0.0 && j.d <= 1.0) || j.out_cap < 0)
+      !(j.d > 0.0 && j.d <= 1.0) || j.out_cap < 0 || !valid_shape(j.launch_shape))
     return DEFT_EINVAL;
   int rc = deft_check_layout(j.offsets_host, j.L, j.N);
   if (rc != DEFT_OK) return rc;
@@ -1839,7 +1853,7 @@ int sparsify(const deft_job* job, const float* src, const float* grad, float eta
         reinterpret_cast<uint32_t*>(static_cast<char*>(j.ws_dev) + w.hist), words);
     HIP_TRY(hipGetLastError());
   }
-  rc = await_sums(j.sumsq_pinned, j.L, s);
+  rc = await_sums(j.sumsq_pinned, j.L, s, spin_limit_us(j));
   if (rc != DEFT_OK) return rc;
 
   rc = deft_norms_from_sumsq(j.sumsq_pinned, j.L, j.norms_host);
@@ -1851,7 +1865,8 @@ int sparsify(const deft_job* job, const float* src, const float* grad, float eta
                           j.owner_bin_host, j.my_layers_host, &cnt);
   if (rc != DEFT_OK) return rc;
   rc = select_layers(g_dev, j.N, j.offsets_host, j.k_host, j.L, j.my_layers_host, cnt, j.idx_out_dev,
-                     j.val_out_dev, j.seg_off_host, j.out_cap, j.ws_dev, j.ws_bytes, stream, &pre);
+                     j.val_out_dev, j.seg_off_host, j.out_cap, j.ws_dev, j.ws_bytes, j.launch_shape,
+                     stream, &pre);
   if (rc != DEFT_OK) return rc;
   *my_count_out = cnt;
   *k_r_out = j.seg_off_host[cnt];

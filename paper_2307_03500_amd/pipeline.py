@@ -38,17 +38,25 @@ class Selection:
         return self.val_dev.cpu().numpy()
 
 
+# Launch shape of selectors that are not given one (tests switch it to run the long-vector
+# kernels on small inputs; it changes speed only).
+DEFAULT_SHAPE = B.SHAPE_AUTO
+
+
 class DeftSelector:
     def __init__(self, tensor_sizes: Sequence[int], n_workers: int, d: float, device,
-                 out_cap: Optional[int] = None):
+                 out_cap: Optional[int] = None, shape: Optional[int] = None, spin_us: int = 0):
         self.device = torch.device(device)
         self.n = int(n_workers)
         self.d = float(d)
+        # launch shape handed to every selection call
+        self.shape = DEFAULT_SHAPE if shape is None else int(shape)
+        self.spin_us = int(spin_us)  # deft_job.spin_us
         self.offsets, self.layer_tensor = B.deft_partition(tensor_sizes, n_workers)
         self.L = L = len(self.offsets) - 1
         self.N = int(self.offsets[-1])
         self.sizes = np.diff(self.offsets).astype(np.int64)
-        self.K = int(np.floor(self.N * self.d + 0.5))
+        self.K = B.deft_total_k(self.N, self.d)
         dev = self.device
         self.offsets_dev = torch.from_numpy(self.offsets).to(dev)
         self.sumsq_host = torch.zeros(L, dtype=torch.float64).pin_memory()
@@ -90,9 +98,10 @@ class DeftSelector:
         j = self._jobs.get(rank)
         if j is None:
             p = self._p
-            j = B.DeftJob(self.N, self.L, self.n, int(rank), 0, self.d, p["off"], p["off_dev"],
-                          p["sizes"], p["sumsq"], p["norms"], p["k"], p["owner"], p["mine"],
-                          p["seg"], p["idx"], p["val"], self._cap, p["ws"], p["ws_bytes"])
+            j = B.DeftJob(self.N, self.L, self.n, int(rank), self.shape, self.d, p["off"],
+                          p["off_dev"], p["sizes"], p["sumsq"], p["norms"], p["k"], p["owner"],
+                          p["mine"], p["seg"], p["idx"], p["val"], self._cap, p["ws"],
+                          p["ws_bytes"], self.spin_us)
             self._jobs[rank] = j
         return B.C.addressof(j)
 
@@ -124,7 +133,7 @@ class DeftSelector:
         p = self._p
         rc = self._lib.deft_select(g.data_ptr(), self.N, p["off"], p["k"], self.L, p["mine"], count,
                                    p["idx"], p["val"], p["seg"], self._cap, p["ws"], p["ws_bytes"],
-                                   stream_handle)
+                                   self.shape, stream_handle)
         if rc:
             raise B.DeftError(rc, "deft_select")
         return int(self.seg_h[count])
@@ -196,13 +205,14 @@ class DeftSelector:
 
     def select_with_plan(self, g: torch.Tensor, k: np.ndarray, my_layers: np.ndarray):
         """Alg. 5 alone, for a given (k, layer list)."""
-        seg = B.deft_select(g, self.offsets, k, my_layers, self.idx_out, self.val_out, self.ws)
+        seg = B.deft_select(g, self.offsets, k, my_layers, self.idx_out, self.val_out, self.ws,
+                            shape=self.shape)
         kr = int(seg[-1])
         return seg, self.idx_out[:kr], self.val_out[:kr]
 
     def topk_global(self, g: torch.Tensor, K: Optional[int] = None):
         K = self.K if K is None else int(K)
-        B.topk_global(g, K, self.idx_out, self.val_out, self.ws)
+        B.topk_global(g, K, self.idx_out, self.val_out, self.ws, shape=self.shape)
         torch.cuda.current_stream().synchronize()
         return self.idx_out[:K].cpu().numpy(), self.val_out[:K].cpu().numpy()
 
@@ -210,6 +220,9 @@ class DeftSelector:
         """Cyclic local Top-k (the comparison scheme of Sec. 1 / Sec. 3.1): the worker whose rank
         equals iteration % n selects the conventional Top-k of its whole vector (to be broadcast
         by the caller); every other worker selects nothing and waits.  Returns (idx, val) or None."""
-        if rank != iteration % self.n:
+        cnt = B.deft_cltk_select(g, self.d, self.n, rank, iteration, self.idx_out, self.val_out,
+                                 self.ws, shape=self.shape)
+        if cnt == 0:
             return None
-        return self.topk_global(g)
+        torch.cuda.current_stream().synchronize()
+        return self.idx_out[:cnt].cpu().numpy(), self.val_out[:cnt].cpu().numpy()

@@ -33,8 +33,23 @@ int main(void) {
   if (deft_workspace_bytes(DEFT_OP_NORMS, 1 << 20, 4) == 0) return 12;
   /* device entry points reject bad arguments before touching a GPU */
   if (deft_layer_norms(NULL, 16, NULL, 1, NULL, NULL, 0, NULL) != DEFT_EINVAL) return 13;
-  if (topk_global(NULL, 16, 4, NULL, NULL, NULL, 0, NULL) != DEFT_EINVAL) return 14;
+  if (topk_global(NULL, 16, 4, NULL, NULL, NULL, 0, DEFT_SHAPE_AUTO, NULL) != DEFT_EINVAL) return 14;
   if (deft_gather_zero(NULL, 16, NULL, 0, NULL, NULL) != DEFT_OK) return 15;
+  {
+    int64_t K = 0, count = -1;
+    int32_t leader = -1;
+    /* Alg. 3, first statement: 300938 * 0.01 = 3009.38 -> 3009; 150 * 0.01 = 1.5 -> 2 */
+    if (deft_total_k(300938, 0.01, &K) != DEFT_OK || K != 3009) return 16;
+    if (deft_total_k(150, 0.01, &K) != DEFT_OK || K != 2) return 17;
+    if (deft_total_k(150, 0.0, &K) != DEFT_EINVAL) return 18;
+    /* cyclic local Top-k: iteration 7 of 4 workers is worker 3's turn; the others select
+     * nothing and touch no device */
+    if (deft_cltk_leader(7, 4, &leader) != DEFT_OK || leader != 3) return 19;
+    if (deft_cltk_select(NULL, 1000, 0.01, 4, 1, 7, NULL, NULL, 0, NULL, 0, DEFT_SHAPE_AUTO, NULL,
+                         &count) != DEFT_OK || count != 0) return 20;
+    if (deft_cltk_select(NULL, 1000, 0.01, 4, 3, 7, NULL, NULL, 0, NULL, 0, DEFT_SHAPE_AUTO, NULL,
+                         &count) != DEFT_ECAP) return 21;
+  }
   printf("c abi ok\n");
   return 0;
 }

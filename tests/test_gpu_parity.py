@@ -89,17 +89,15 @@ def test_deft_path_configs_all_ranks(deft, name):
     off = sel.offsets.tolist()
     lay = sel.sizes.tolist()
     o_norms = O.layer_norms(gs.g, off)
-    o_k = O.alloc_k(o_norms, lay, gs.N, gs.d)
     seen = []
     for r in range(gs.n_workers):
         res = sel.select(gd, rank=r, iteration=0)
         _check_norms(res.norms, o_norms)
-        # host plan from the GPU's own norms: bit-exact against the oracle fed the same norms
-        assert res.k.tolist() == O.alloc_k(res.norms, lay, gs.N, gs.d)
-        o_owner, o_part, _ = O.assign_layers(lay, res.k.tolist(), gs.n_workers, 0, r)
+        # host plan from the GPU's own norms: bit-exact against the oracle fed the same norms;
+        # end to end (oracle norms) the same plan unless a k_temp sits on an integer
+        o_k = _plan_k(res, o_norms, lay, gs.N, gs.d)
+        o_owner, o_part, _ = O.assign_layers(lay, o_k, gs.n_workers, 0, r)
         assert res.owner_bin.tolist() == o_owner and res.my_layers.tolist() == o_part
-        # end to end: the plan from oracle norms is the same plan
-        assert res.k.tolist() == o_k
         o_idx, o_val, o_seg = O.select(gs.g, off, o_k, o_part)
         assert res.seg_off.tolist() == o_seg.tolist()
         assert res.idx.tolist() == o_idx.tolist()
@@ -109,15 +107,14 @@ def test_deft_path_configs_all_ranks(deft, name):
     assert len(np.unique(allidx)) == len(allidx) == sum(o_k)
 
 
-@pytest.mark.parametrize("spin_us", ["20000", "0"])
+@pytest.mark.parametrize("spin_us", [0, -1])
 @pytest.mark.parametrize("name", ["toy_mlp", "resnet18", "lstm_lm"])
-def test_sparsify_single_entry_matches_oracle(deft, monkeypatch, name, spin_us):
+def test_sparsify_single_entry_matches_oracle(deft, name, spin_us):
     """deft_sparsify (one call for Sec. 4's four steps) against the oracle, with the wait on
-    the pinned sums (spin) and with the stream-synchronise fallback (DEFT_SPIN_US=0); the
-    iteration argument rotates the bins (Alg. 4)."""
-    monkeypatch.setenv("DEFT_SPIN_US", spin_us)
+    the pinned sums (job.spin_us = 0: poll for the default time) and with the stream-synchronise
+    fallback (spin_us < 0: no polling); the iteration argument rotates the bins (Alg. 4)."""
     gs = synth.make(name, seed=1)
-    sel = _selector(deft, gs.tensor_sizes, gs.n_workers, gs.d)
+    sel = pipeline.DeftSelector(gs.tensor_sizes, gs.n_workers, gs.d, DEV, spin_us=spin_us)
     gd = torch.from_numpy(gs.g).to(DEV)
     off, lay = sel.offsets.tolist(), sel.sizes.tolist()
     o_norms = O.layer_norms(gs.g, off)
@@ -335,10 +332,10 @@ def test_select_repeatable_and_workspace_reuse(deft):
 @pytest.fixture
 def long_vector_shape():
     """Force the long-vector launch shape on small inputs (it changes speed only)."""
-    import os
-    os.environ["DEFT_LONG_VECTOR_ELEMS"] = "0"
+    from paper_2307_03500_amd import binding, pipeline
+    pipeline.DEFAULT_SHAPE = binding.SHAPE_LONG
     yield
-    del os.environ["DEFT_LONG_VECTOR_ELEMS"]
+    pipeline.DEFAULT_SHAPE = binding.SHAPE_AUTO
 
 
 @pytest.mark.parametrize("frac", [20, 3])
@@ -520,35 +517,95 @@ def _verify_topk_by_threshold(g, idx, val, s, e, k):
     assert (want == idx).all()
 
 
+def _plan_k(res, o_norms, lay, N, d):
+    """The k of a result against Alg. 3 of the oracle.  k is a discontinuous function of the
+    norms, and the two sides' norms agree to ~1e-15 relative, not bit for bit: the library's k
+    must equal the oracle's k from the SAME (GPU) norms always; it equals the oracle's k from the
+    oracle's own norms unless some k_temp sits within that error of an integer, which is then
+    reported as such rather than hidden.  Returns the k both sides use from here on."""
+    k_same = O.alloc_k(res.norms, lay, N, d)
+    assert res.k.tolist() == k_same
+    k_own = O.alloc_k(o_norms, lay, N, d)
+    if k_same != k_own:
+        diff = [l for l in range(len(lay)) if k_same[l] != k_own[l]]
+        assert all(abs(k_same[l] - k_own[l]) <= 1 for l in diff), "not a rounding-induced difference"
+        print("norm-induced k difference in layers", diff)
+    return k_same
+
+
 @pytest.mark.parametrize("name,ranks", [("bert_base", [0, 7, 15]), ("gpt2_medium", [0, 13])])
 def test_full_size_configs(deft, name, ranks):
+    """The two sets that exceed the last-level cache, at full size, in the launch configuration
+    the benchmark times.  Every listed rank's layer-wise selection is compared with the sorting
+    oracle element by element, and so is the conventional Top-k over all 109 M elements of the
+    BERT-shaped set.  The conventional Top-k over the 355 M-element GPT-2-shaped set is checked
+    by the threshold property instead (complete: it admits exactly one index set), because the
+    oracle's stable 64-bit sort of 355 M keys takes several minutes and 9 GB on the test host."""
     gs = synth.make(name, seed=0)
     sel = _selector(deft, gs.tensor_sizes, gs.n_workers, gs.d)
     gd = torch.from_numpy(gs.g).to(DEV)
     off = sel.offsets.tolist()
     lay = sel.sizes.tolist()
     o_norms = O.layer_norms(gs.g, off)
-    o_k = O.alloc_k(o_norms, lay, gs.N, gs.d)
     for r in ranks:
+        print("full size", name, "rank", r, flush=True)
         res = sel.select(gd, rank=r)
         _check_norms(res.norms, o_norms)
-        assert res.k.tolist() == o_k
+        o_k = _plan_k(res, o_norms, lay, gs.N, gs.d)
         o_owner, o_part, _ = O.assign_layers(lay, o_k, gs.n_workers, 0, r)
         assert res.owner_bin.tolist() == o_owner and res.my_layers.tolist() == o_part
         idx, val = res.idx, res.val
-        for j, p in enumerate(o_part):
-            a, b = int(res.seg_off[j]), int(res.seg_off[j + 1])
-            _verify_topk_by_threshold(gs.g, idx[a:b].astype(np.int64), val[a:b], off[p], off[p + 1], o_k[p])
-        if r == ranks[0]:  # one rank also against the sorting oracle itself
-            o_idx, o_val, _ = O.select(gs.g, off, o_k, o_part)
-            assert (idx == o_idx).all() and (_bits(val) == _bits(o_val)).all()
+        o_idx, o_val, o_seg = O.select(gs.g, off, o_k, o_part)
+        assert res.seg_off.tolist() == o_seg.tolist()
+        assert (idx == o_idx).all() and (_bits(val) == _bits(o_val)).all()
         # the single entry point (the call the benchmark times) returns the same bits
         one = sel.sparsify(gd, rank=r)
         assert one.k.tolist() == o_k and one.my_layers.tolist() == o_part
         assert one.seg_off.tolist() == res.seg_off.tolist()
         assert (one.idx == idx).all() and (_bits(one.val) == _bits(val)).all()
+    print("full size", name, "conventional Top-k", flush=True)
     gi, gv = sel.topk_global(gd)
-    _verify_topk_by_threshold(gs.g, gi.astype(np.int64), gv, 0, gs.N, sel.K)
+    if name == "bert_base":
+        oi, ov = O.topk_global(gs.g, O.total_k(gs.N, gs.d))
+        assert (gi == oi).all() and (_bits(gv) == _bits(ov)).all()
+    else:
+        _verify_topk_by_threshold(gs.g, gi.astype(np.int64), gv, 0, gs.N, sel.K)
+
+
+def test_error_feedback_iteration_at_full_size(deft):
+    """Alg. 1 around the sparsifier on the 355 M-element GPT-2-shaped set, worker 0 of 32: the
+    fused accumulate + norm pass + selection (deft_accumulate_sparsify) and the gather + zero step
+    (deft_gather_zero) against the oracle, bit for bit -- the size the quoted timings of these two
+    calls are measured at."""
+    gs = synth.make("gpt2_medium", seed=0)
+    n, d, N = gs.n_workers, gs.d, gs.N
+    sel = _selector(deft, gs.tensor_sizes, n, d)
+    off, lay = sel.offsets.tolist(), sel.sizes.tolist()
+    e = np.roll(gs.g, 12345) * np.float32(0.25)      # a carried error of comparable magnitude
+    eta = 0.1
+    e_d = torch.from_numpy(e).to(DEV)
+    g_d = torch.from_numpy(gs.g).to(DEV)
+    print("full-size error feedback: GPU", flush=True)
+    res = sel.accumulate_sparsify(e_d, g_d, eta, e_d, rank=0, iteration=0)   # in place
+    idx_d = res.idx_dev.clone()
+    vals_d = torch.empty(idx_d.numel(), dtype=torch.float32, device=DEV)
+    acc_before = e_d.cpu().numpy()
+    deft.deft_gather_zero(e_d, idx_d, vals_d)
+    torch.cuda.synchronize()
+    print("full-size error feedback: oracle", flush=True)
+    o_acc = O.accumulate(e, gs.g, eta)
+    assert (_bits(acc_before) == _bits(o_acc)).all()
+    o_norms = O.layer_norms(o_acc, off)
+    _check_norms(res.norms, o_norms)
+    o_k = _plan_k(res, o_norms, lay, N, d)
+    o_owner, o_part, _ = O.assign_layers(lay, o_k, n, 0, 0)
+    assert res.owner_bin.tolist() == o_owner and res.my_layers.tolist() == o_part
+    o_idx, o_val, o_seg = O.select(o_acc, off, o_k, o_part)
+    assert res.seg_off.tolist() == o_seg.tolist()
+    assert (res.idx == o_idx).all() and (_bits(res.val) == _bits(o_val)).all()
+    o_vals, o_next = O.gather_zero(o_acc, o_idx)
+    assert (_bits(vals_d.cpu().numpy()) == _bits(o_vals)).all()
+    assert (_bits(e_d.cpu().numpy()) == _bits(o_next)).all()
 
 
 def test_maximum_vector_length(deft):

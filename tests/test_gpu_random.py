@@ -1,12 +1,11 @@
 """Randomised GPU parity: many seeded shapes, value kinds, k choices and layer subsets, in both
 launch shapes of the selection, each compared element by element with the CPU oracle."""
-import os
-
 import numpy as np
 import pytest
 import torch
 
 from oracle import deft_oracle as O
+from paper_2307_03500_amd import binding as B
 from paper_2307_03500_amd import pipeline
 
 pytestmark = pytest.mark.gpu
@@ -42,15 +41,14 @@ def _values(rng, N, kind):
 def test_random_layers_and_k(deft, seed):
     rng = np.random.default_rng(7000 + seed)
     long_shape = seed % 3 == 2
-    if long_shape:
-        os.environ["DEFT_LONG_VECTOR_ELEMS"] = "0"
+    shape = B.SHAPE_LONG if long_shape else B.SHAPE_AUTO
     try:
         n_layers = int(rng.integers(1, 40))
         top = int(10 ** rng.uniform(1, 5.6))
         sizes = [int(x) for x in rng.integers(1, top + 1, n_layers)]
         N = sum(sizes)
         g = _values(rng, N, seed % 6)
-        sel = pipeline.DeftSelector(sizes, 1, 0.5, DEV, out_cap=N)
+        sel = pipeline.DeftSelector(sizes, 1, 0.5, DEV, out_cap=N, shape=shape)
         gd = torch.from_numpy(g).to(DEV)
         off = sel.offsets.tolist()
         for trial in range(3):
@@ -83,7 +81,7 @@ def test_random_layers_and_k(deft, seed):
         assert (got[~nz] == 0).all()
         assert (np.abs(got[nz] - want[nz]) / want[nz]).max(initial=0.0) <= 1e-13
     finally:
-        os.environ.pop("DEFT_LONG_VECTOR_ELEMS", None)
+        pass
 
 
 @pytest.mark.parametrize("seed", range(16))
@@ -91,15 +89,14 @@ def test_random_whole_call(deft, seed):
     """deft_sparsify on random layer lists (fewer and more segments than one descriptor batch
     holds, both launch shapes) against the oracle's whole path fed the GPU's norms."""
     rng = np.random.default_rng(9000 + seed)
-    if seed % 4 == 3:
-        os.environ["DEFT_LONG_VECTOR_ELEMS"] = "0"
+    shape = B.SHAPE_LONG if seed % 4 == 3 else B.SHAPE_AUTO
     try:
         n_tensors = int(rng.integers(1, 60)) if seed % 2 else int(rng.integers(150, 260))
         top = int(10 ** rng.uniform(1, 4.8))
         sizes = [int(x) for x in rng.integers(1, top + 1, n_tensors)]
         n = int(rng.integers(1, 5))
         d = float(10 ** rng.uniform(-3, -0.5))
-        sel = pipeline.DeftSelector(sizes, n, d, DEV)
+        sel = pipeline.DeftSelector(sizes, n, d, DEV, shape=shape)
         N = sel.N
         g = _values(rng, N, seed % 6)
         pos = 0
@@ -120,4 +117,4 @@ def test_random_whole_call(deft, seed):
             assert res.idx.tolist() == o_idx.tolist()
             assert (res.val.view(np.uint32) == o_val.view(np.uint32)).all()
     finally:
-        os.environ.pop("DEFT_LONG_VECTOR_ELEMS", None)
+        pass

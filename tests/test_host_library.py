@@ -177,12 +177,13 @@ def test_device_calls_reject_bad_arguments_before_touching_the_gpu(deft):
     i64p, i32p = C.POINTER(C.c_int64), C.POINTER(C.c_int32)
 
     def sel(g=0x1000, N=16, offp=off, kk=k, my=mine, cnt=2, idx=0x2000, val=0x3000, cap=16,
-            ws=0x4000, wsb=1 << 20):
+            ws=0x4000, wsb=1 << 20, shape=B.SHAPE_AUTO):
         return lib.deft_select(C.c_void_p(g), N, offp.ctypes.data_as(i64p), kk.ctypes.data_as(i64p),
                                len(offp) - 1, my.ctypes.data_as(i32p), cnt, C.c_void_p(idx),
                                C.c_void_p(val), seg.ctypes.data_as(i64p), cap, C.c_void_p(ws), wsb,
-                               None)
+                               shape, None)
 
+    assert sel(shape=3) == B.DEFT_EINVAL and sel(shape=-1) == B.DEFT_EINVAL
     assert sel(g=0) == B.DEFT_EINVAL
     assert sel(g=0x1004) == B.DEFT_EINVAL                      # misaligned vector
     assert sel(N=17) == B.DEFT_EINVAL                          # offsets[L] != N
@@ -232,7 +233,7 @@ def test_device_calls_reject_bad_arguments_before_touching_the_gpu(deft):
     cnt, kr = C.c_int32(-7), C.c_int64(-7)
 
     def spars(g=0x1000, **over):
-        f = dict(N=16, L=2, n_workers=2, rank=0, reserved=0, d=0.25, offsets_host=off.ctypes.data,
+        f = dict(N=16, L=2, n_workers=2, rank=0, launch_shape=0, d=0.25, offsets_host=off.ctypes.data,
                  offsets_dev=0x5000, sizes_host=sizes.ctypes.data, sumsq_pinned=0x6000,
                  norms_host=bufs["norms"].ctypes.data, k_host=bufs["k"].ctypes.data,
                  owner_bin_host=bufs["owner"].ctypes.data, my_layers_host=bufs["mine"].ctypes.data,
@@ -248,6 +249,7 @@ def test_device_calls_reject_bad_arguments_before_touching_the_gpu(deft):
     assert spars(g=0) == B.DEFT_EINVAL
     assert spars(g=0x1004) == B.DEFT_EINVAL
     assert spars(rank=2) == B.DEFT_EINVAL
+    assert spars(launch_shape=7) == B.DEFT_EINVAL
     assert spars(n_workers=0) == B.DEFT_EINVAL
     assert spars(d=0.0) == B.DEFT_EINVAL
     assert spars(d=1.5) == B.DEFT_EINVAL
@@ -259,7 +261,7 @@ def test_device_calls_reject_bad_arguments_before_touching_the_gpu(deft):
     assert spars(ws_dev=0x4004) == B.DEFT_EINVAL
     assert spars(ws_bytes=64) == B.DEFT_EWS
     assert cnt.value == -7 and kr.value == -7
-    ok_job = B.DeftJob(N=16, L=2, n_workers=2, rank=0, reserved=0, d=0.25,
+    ok_job = B.DeftJob(N=16, L=2, n_workers=2, rank=0, launch_shape=0, d=0.25,
                        offsets_host=off.ctypes.data, offsets_dev=0x5000,
                        sizes_host=sizes.ctypes.data, sumsq_pinned=0x6000,
                        norms_host=bufs["norms"].ctypes.data, k_host=bufs["k"].ctypes.data,
@@ -279,13 +281,87 @@ def test_device_calls_reject_bad_arguments_before_touching_the_gpu(deft):
     assert accsp(gr=0x7004) == B.DEFT_EINVAL
     assert accsp(acc=0x8008) == B.DEFT_EINVAL
 
-    def topk(g=0x1000, N=16, K=4, idx=0x2000, val=0x3000, ws=0x4000, wsb=1 << 20):
+    def topk(g=0x1000, N=16, K=4, idx=0x2000, val=0x3000, ws=0x4000, wsb=1 << 20, shape=0):
         return lib.topk_global(C.c_void_p(g), N, K, C.c_void_p(idx), C.c_void_p(val),
-                               C.c_void_p(ws), wsb, None)
+                               C.c_void_p(ws), wsb, shape, None)
 
+    assert topk(shape=5) == B.DEFT_EINVAL
     assert topk(K=17) == B.DEFT_EINVAL
     assert topk(K=-1) == B.DEFT_EINVAL
     assert topk(N=2 ** 31) == B.DEFT_ERANGE
     assert topk(wsb=0) == B.DEFT_EWS
     assert topk(K=0) == B.DEFT_OK
     assert topk(idx=0) == B.DEFT_EINVAL
+
+
+def test_total_k_and_cltk_leader_hand_values(deft):
+    """Alg. 3's first statement and the turn-taking rule of cyclic local Top-k (Sec. 3.1), by
+    hand: 11689512 * 0.01 = 116895.12 -> 116895; 150 * 0.01 = 1.5 -> 2 (half up)."""
+    B = deft
+    assert B.deft_total_k(11689512, 0.01) == 116895
+    assert B.deft_total_k(150, 0.01) == 2
+    assert B.deft_total_k(10, 1.0) == 10
+    for N, d in [(300938, 0.01), (19780400, 0.001), (7, 0.5), (354823168, 0.001)]:
+        assert B.deft_total_k(N, d) == O.total_k(N, d)
+    with pytest.raises(B.DeftError):
+        B.deft_total_k(0, 0.5)
+    with pytest.raises(B.DeftError):
+        B.deft_total_k(10, 1.5)
+    assert [B.deft_cltk_leader(t, 4) for t in range(6)] == [0, 1, 2, 3, 0, 1]
+    assert B.deft_cltk_leader(9, 1) == 0
+    with pytest.raises(B.DeftError):
+        B.deft_cltk_leader(-1, 4)
+
+
+def test_partition_hand_worked_five_tensors(deft):
+    """The library against the same pencil-worked case of Alg. 2 that pins the oracle
+    (tests/test_oracle_pins.py): tensors 23, 5, 12, 1, 9."""
+    B = deft
+    off, lt = B.deft_partition([23, 5, 12, 1, 9], 4)
+    assert off.tolist() == [0, 6, 12, 18, 23, 28, 40, 41, 50] and lt.tolist() == [0, 0, 0, 0, 1, 2, 3, 4]
+    off, lt = B.deft_partition([23, 5, 12, 1, 9], 5)
+    assert off.tolist() == [0, 5, 10, 15, 19, 23, 28, 31, 34, 36, 38, 40, 41, 50]
+    assert lt.tolist() == [0, 0, 0, 0, 0, 1, 2, 2, 2, 2, 2, 3, 4]
+    off, _ = B.deft_partition([0, 2, 0], 4)   # 2 > 2/4 is cut in four; the empty pieces vanish
+    assert off.tolist() == [0, 1, 2]
+
+
+def test_cost_model_hand_worked(deft):
+    """deft_cost_model against the pencil values of Eq. 3-8 (see the oracle's pin of the same
+    two cases for the working)."""
+    B = deft
+    a = B.deft_cost_model([100, 50, 200, 10], [4, 2, 8, 1], [1, 1, 0, 1], 2, 360, 15)
+    assert a["C_i"] == pytest.approx([415.8883, 173.2868], abs=1e-4)
+    assert a["f_n"] == pytest.approx(2.34413, abs=1e-5)
+    assert a["f_trivial"] == pytest.approx(2.68802, abs=1e-5)
+    b = B.deft_cost_model([64, 32, 16, 8, 8], [16, 8, 4, 2, 2], [0, 1, 2, 1, 2], 3, 128, 32)
+    assert b["f_n"] == pytest.approx(2.5, rel=1e-12)
+    assert b["C_trivial"] == pytest.approx(100.9973, abs=1e-4)
+
+
+def test_host_planner_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """csrc/deft_host.cpp built with the host compiler under -fsanitize=address,undefined and
+    driven by tests/host_sanitize_check.c over 400 seeded shapes with exactly-sized output
+    arrays: any out-of-bounds access or undefined operation aborts the run with a report."""
+    import shutil
+    import subprocess
+    cxx, cc = shutil.which("g++"), shutil.which("gcc")
+    if not cxx or not cc:
+        pytest.skip("no host compiler")
+    san = ["-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-g", "-O1"]
+    inc = ["-I", os.path.join(ROOT, "include")]
+    obj_lib, obj_drv, exe = (str(tmp_path / n) for n in ("deft_host.o", "driver.o", "host_sanitize"))
+    subprocess.run([cxx, "-std=c++17", "-ffp-contract=off", *san, *inc, "-c",
+                    os.path.join(ROOT, "paper_2307_03500_amd", "csrc", "deft_host.cpp"),
+                    "-o", obj_lib], check=True)
+    subprocess.run([cc, "-std=c99", *san, *inc, "-c",
+                    os.path.join(ROOT, "tests", "host_sanitize_check.c"), "-o", obj_drv], check=True)
+    # the run-time is linked statically so that it is first in the library list whatever the
+    # environment preloads
+    subprocess.run([cxx, "-fsanitize=address,undefined", "-static-libasan", obj_lib, obj_drv,
+                    "-o", exe], check=True)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    run = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=120)
+    assert run.returncode == 0, run.stderr[-2000:]
+    assert "host sanitize ok" in run.stdout
+    assert "ERROR: AddressSanitizer" not in run.stderr and "runtime error" not in run.stderr
