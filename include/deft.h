@@ -51,6 +51,7 @@ extern "C" {
 #define DEFT_EWS (-3)    /* workspace too small (see deft_workspace_bytes) */
 #define DEFT_ECAP (-4)   /* output capacity too small */
 #define DEFT_EHIP (-5)   /* HIP launch/runtime error */
+#define DEFT_ELIMIT (-6) /* size beyond the built-in scratch of deft_layer_norms_noalloc */
 
 #define DEFT_SHAPE_AUTO 0
 #define DEFT_SHAPE_SHORT 1
@@ -99,6 +100,24 @@ int deft_check_layout(const int64_t* offsets_host, int32_t L, int64_t N);
  */
 int deft_layer_norms(const float* g_dev, int64_t N, const int64_t* offsets_dev, int32_t L,
                      double* sumsq_dev, void* ws_dev, size_t ws_bytes, void* stream);
+
+/*
+ * deft_layer_norms for callers that can neither allocate device memory nor bring a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * kernels, same results, same arguments minus the workspace: the per-chunk partial sums go to
+ * an array built into the library's device image (4 MiB on every GPU the library runs on, held
+ * until the process ends).  The call allocates and frees nothing.
+ *   N  at most DEFT_NOALLOC_MAX_ELEMS (2^30 elements); beyond that DEFT_ELIMIT, nothing enqueued
+ * The first call on a device looks up the array's address there (once per device; make that call
+ * before a capture begins).  All calls on one GPU share that GPU's array: calls whose kernels
+ * may overlap on one GPU (different streams, no ordering between them) race on it -- order them.
+ * The array keeps the previous call's partial sums; every entry a call reads it has written
+ * itself first, so nothing needs clearing.
+ * Errors: DEFT_EINVAL, DEFT_ERANGE, DEFT_ELIMIT, DEFT_EHIP.
+ */
+#define DEFT_NOALLOC_MAX_ELEMS (1ll << 30)
+int deft_layer_norms_noalloc(const float* g_dev, int64_t N, const int64_t* offsets_dev, int32_t L,
+                             double* sumsq_dev, void* stream);
 
 /*
  * First statement of Alg. 3 (k = n_g * d; density is defined in the footnote of Sec. 1):

@@ -14,7 +14,8 @@ import numpy as np
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdeft.so")
 
-DEFT_OK, DEFT_EINVAL, DEFT_ERANGE, DEFT_EWS, DEFT_ECAP, DEFT_EHIP = 0, -1, -2, -3, -4, -5
+DEFT_OK, DEFT_EINVAL, DEFT_ERANGE, DEFT_EWS, DEFT_ECAP, DEFT_EHIP, DEFT_ELIMIT = 0, -1, -2, -3, -4, -5, -6
+NOALLOC_MAX_ELEMS = 1 << 30
 OP_NORMS, OP_SELECT, OP_TOPK_GLOBAL = 0, 1, 2
 SHAPE_AUTO, SHAPE_SHORT, SHAPE_LONG = 0, 1, 2
 
@@ -27,6 +28,7 @@ SIGNATURES = {
     "deft_partition": (C.c_int, [_P, C.c_int32, C.c_int32, _P, _P, C.c_int32, _P]),
     "deft_check_layout": (C.c_int, [_P, C.c_int32, C.c_int64]),
     "deft_layer_norms": (C.c_int, [_P, C.c_int64, _P, C.c_int32, _P, _P, C.c_size_t, _P]),
+    "deft_layer_norms_noalloc": (C.c_int, [_P, C.c_int64, _P, C.c_int32, _P, _P]),
     "deft_norms_from_sumsq": (C.c_int, [_P, C.c_int32, _P]),
     "deft_total_k": (C.c_int, [C.c_int64, C.c_double, _P]),
     "deft_cltk_leader": (C.c_int, [C.c_int64, C.c_int32, _P]),
@@ -189,6 +191,14 @@ def deft_layer_norms(g, offsets_dev, sumsq, ws, stream=None) -> None:
                                   sumsq.data_ptr(), ws.data_ptr(),
                                   ws.numel() * ws.element_size(), _stream(stream)),
            "deft_layer_norms")
+
+
+def deft_layer_norms_noalloc(g, offsets_dev, sumsq, stream=None) -> None:
+    """deft_layer_norms without a workspace argument (scratch built into the library)."""
+    L = offsets_dev.numel() - 1
+    _check(lib().deft_layer_norms_noalloc(g.data_ptr(), g.numel(), offsets_dev.data_ptr(), L,
+                                          sumsq.data_ptr(), _stream(stream)),
+           "deft_layer_norms_noalloc")
 
 
 def deft_accumulate_norms(e, grad, eta: float, acc, offsets_dev, sumsq, ws, stream=None) -> None:

@@ -22,6 +22,7 @@ extern "C" const char* deft_strerror(int status) {
     case DEFT_EWS: return "workspace too small";
     case DEFT_ECAP: return "output capacity too small";
     case DEFT_EHIP: return "HIP runtime error";
+    case DEFT_ELIMIT: return "vector longer than the built-in scratch of the no-allocation entry point allows";
     default: return "unknown status";
   }
 }

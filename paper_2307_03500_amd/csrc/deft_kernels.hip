@@ -30,6 +30,7 @@
 #include <atomic>
 #include <chrono>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 namespace {
@@ -1599,18 +1600,11 @@ extern "C" size_t deft_workspace_bytes(int op, int64_t elems, int32_t count) {
 }
 
 namespace {
-int run_norms(const float* g, const float* grad, float eta, float* acc, int64_t N,
-              const int64_t* offsets_dev, int32_t L, double* sumsq_dev, void* ws_dev,
-              size_t ws_bytes, void* stream) {
-  if (!g || !offsets_dev || !sumsq_dev || !ws_dev || L < 1 || N < 1) return DEFT_EINVAL;
-  if (N > kMaxN) return DEFT_ERANGE;
-  if ((reinterpret_cast<uintptr_t>(g) & 15u) || (reinterpret_cast<uintptr_t>(ws_dev) & 15u))
-    return DEFT_EINVAL;
-  if (ws_bytes < deft_workspace_bytes(DEFT_OP_NORMS, N, L)) return DEFT_EWS;
+// Enqueues the norm pass with its per-chunk partial sums in head[chunks], tail[chunks].
+int launch_norms(const float* g, const float* grad, float eta, float* acc, int64_t N,
+                 const int64_t* offsets_dev, int32_t L, double* sumsq_dev, double* head,
+                 double* tail, hipStream_t s) {
   const unsigned chunks = (unsigned)((N + kNormChunk - 1) / kNormChunk);
-  double* head = static_cast<double*>(ws_dev);
-  double* tail = head + chunks;
-  hipStream_t s = static_cast<hipStream_t>(stream);
   NormSrc src;
   src.g = g; src.gr = grad; src.acc = acc; src.eta = eta;
   if (acc)
@@ -1620,6 +1614,20 @@ int run_norms(const float* g, const float* grad, float eta, float* acc, int64_t 
   norm_finish_kernel<<<L, kThreads, 0, s>>>(offsets_dev, N, head, tail, sumsq_dev);
   HIP_TRY(hipGetLastError());
   return DEFT_OK;
+}
+
+int run_norms(const float* g, const float* grad, float eta, float* acc, int64_t N,
+              const int64_t* offsets_dev, int32_t L, double* sumsq_dev, void* ws_dev,
+              size_t ws_bytes, void* stream) {
+  if (!g || !offsets_dev || !sumsq_dev || !ws_dev || L < 1 || N < 1) return DEFT_EINVAL;
+  if (N > kMaxN) return DEFT_ERANGE;
+  if ((reinterpret_cast<uintptr_t>(g) & 15u) || (reinterpret_cast<uintptr_t>(ws_dev) & 15u))
+    return DEFT_EINVAL;
+  if (ws_bytes < deft_workspace_bytes(DEFT_OP_NORMS, N, L)) return DEFT_EWS;
+  const size_t chunks = (size_t)((N + kNormChunk - 1) / kNormChunk);
+  double* head = static_cast<double*>(ws_dev);
+  return launch_norms(g, grad, eta, acc, N, offsets_dev, L, sumsq_dev, head, head + chunks,
+                      static_cast<hipStream_t>(stream));
 }
 }  // namespace
 
@@ -1888,4 +1896,55 @@ extern "C" int deft_accumulate_sparsify(const deft_job* job, const float* e_dev,
   if (!grad_dev || !acc_dev) return DEFT_EINVAL;
   return sparsify(job, e_dev, grad_dev, eta, acc_dev, iteration, stream, norms_done_event,
                   my_count_out, k_r_out);
+}
+
+// ------------------------------------------------------------------------------------------
+// The norm pass for callers that cannot allocate or bring a workspace: its per-chunk partial
+// sums live in a file-scope device array.
+// ------------------------------------------------------------------------------------------
+namespace {
+constexpr int64_t kStaticNormMaxElems = DEFT_NOALLOC_MAX_ELEMS;
+constexpr size_t kStaticNormChunks = (size_t)((kStaticNormMaxElems + kNormChunk - 1) / kNormChunk);
+constexpr int kMaxDevices = 64;
+}  // namespace
+
+// head[kStaticNormChunks] followed by tail[kStaticNormChunks]: 4 MiB on every GPU the library
+// runs on, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; the device address it resolves to is what kernels and copies receive.
+static __device__ __align__(256) double scratch[2 * kStaticNormChunks];
+
+namespace {
+std::mutex g_scratch_mutex;
+double* g_scratch_ptr[kMaxDevices] = {};  // per device: each GPU holds its own copy of the array
+
+// Device address of `scratch` on the current device, resolved once per device.
+int static_scratch(double** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return DEFT_EHIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    double* ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch)));
+    if (!ptr) return DEFT_EHIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return DEFT_OK;
+}
+}  // namespace
+
+extern "C" int deft_layer_norms_noalloc(const float* g_dev, int64_t N, const int64_t* offsets_dev,
+                                        int32_t L, double* sumsq_dev, void* stream) {
+  if (!g_dev || !offsets_dev || !sumsq_dev || L < 1 || N < 1) return DEFT_EINVAL;
+  if (N > kMaxN) return DEFT_ERANGE;
+  if (N > kStaticNormMaxElems) return DEFT_ELIMIT;
+  if (reinterpret_cast<uintptr_t>(g_dev) & 15u) return DEFT_EINVAL;
+  double* ptr = nullptr;
+  const int rc = static_scratch(&ptr);
+  if (rc != DEFT_OK) return rc;
+  // Every chunk of this call writes its head and tail entry before norm_finish_kernel reads
+  // them, so what an earlier call left in the array needs no clearing.
+  return launch_norms(g_dev, nullptr, 0.0f, nullptr, N, offsets_dev, L, sumsq_dev, ptr,
+                      ptr + kStaticNormChunks, static_cast<hipStream_t>(stream));
 }
