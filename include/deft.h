@@ -33,7 +33,9 @@
  *   - The library reads no environment variable and has no settings of its own: what tunes a
  *     call travels in its arguments.  The selection calls take a launch shape: DEFT_SHAPE_AUTO
  *     picks by size (long-vector kernels above 2^25 selected-from elements); DEFT_SHAPE_SHORT and
- *     DEFT_SHAPE_LONG force one.  The shape changes speed only, never results.
+ *     DEFT_SHAPE_LONG force one; _LONG_PLAIN and _LONG_SAMPLED also fix whether the long-vector
+ *     kernels sample a segment ahead of their first pass (by default they do where it pays).
+ *     The shape changes speed only, never results.
  */
 #ifndef DEFT_H
 #define DEFT_H
@@ -56,6 +58,20 @@ extern "C" {
 #define DEFT_SHAPE_AUTO 0
 #define DEFT_SHAPE_SHORT 1
 #define DEFT_SHAPE_LONG 2
+#define DEFT_SHAPE_LONG_PLAIN 3   /* long-vector kernels, no sampling ahead of the first pass */
+#define DEFT_SHAPE_LONG_SAMPLED 4 /* long-vector kernels, every segment sampled if it can be */
+
+/*
+ * After a selection call that ran the long-vector kernels, the first DEFT_STAT_WORDS 32-bit words
+ * of its workspace tell how the segments' first pass went (diagnostics; valid once the stream is
+ * synchronised): how many segments had the threshold placed by a sample and were read once, how
+ * many of those had to be redone in full because the exact check refuted the sample, and how many
+ * were treated in full from the start (all three are zero after a call that sampled nothing).
+ */
+#define DEFT_STAT_BOUNDED 0
+#define DEFT_STAT_REDONE 1
+#define DEFT_STAT_FULL 2
+#define DEFT_STAT_WORDS 4
 
 #define DEFT_OP_NORMS 0
 #define DEFT_OP_SELECT 1
@@ -187,7 +203,7 @@ int deft_cost_model(const int64_t* sizes, const int64_t* k, const int32_t* owner
  *   out_cap            in   capacity of idx/val in entries; must be >= sum of the k's
  *   ws_dev             scratch, deft_workspace_bytes(DEFT_OP_SELECT, share, my_count) bytes
  *                      where share >= total size of the caller's layers; 16-byte aligned
- *   launch_shape       in   DEFT_SHAPE_AUTO, _SHORT or _LONG
+ *   launch_shape       in   one of the DEFT_SHAPE_ values
  * my_count == 0 is valid and enqueues nothing.
  * Errors: DEFT_EINVAL, DEFT_ERANGE, DEFT_EWS, DEFT_ECAP, DEFT_EHIP.
  */
@@ -265,7 +281,7 @@ int deft_gather_zero(float* acc_dev, int64_t N, const int32_t* idx_dev, int64_t 
  *
  * deft_job holds what stays the same from call to call; the caller fills it once.
  *   N, L, n_workers, rank, d     the job (d in (0,1], rank in [0, n_workers))
- *   launch_shape                 DEFT_SHAPE_AUTO, _SHORT or _LONG, as for deft_select
+ *   launch_shape                 one of the DEFT_SHAPE_ values, as for deft_select
  *   spin_us                      how long to poll for the sums before blocking in the stream
  *                                synchronisation: 0 = default (20000), negative = do not poll
  *   offsets_host / offsets_dev   the same L+1 offsets in host and in device memory

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdeft.so"
 DEFT_OK, DEFT_EINVAL, DEFT_ERANGE, DEFT_EWS, DEFT_ECAP, DEFT_EHIP, DEFT_ELIMIT = 0, -1, -2, -3, -4, -5, -6
 NOALLOC_MAX_ELEMS = 1 << 30
 OP_NORMS, OP_SELECT, OP_TOPK_GLOBAL = 0, 1, 2
-SHAPE_AUTO, SHAPE_SHORT, SHAPE_LONG = 0, 1, 2
+SHAPE_AUTO, SHAPE_SHORT, SHAPE_LONG, SHAPE_LONG_PLAIN, SHAPE_LONG_SAMPLED = 0, 1, 2, 3, 4
 
 # Every pointer travels as a plain address (void*): numpy arrays pass `arr.ctypes.data`,
 # torch tensors pass `t.data_ptr()`; callers on a hot path cache those integers.

@@ -41,7 +41,10 @@ constexpr int64_t kMaxN = (int64_t(1) << 31) - 1;
 constexpr uint32_t kMaxSlotCap = kThreads;  // one thread per slot entry in the slot kernels
 // Workgroups of the long-vector first pass: at least the resident set (256 CUs x 3), so every
 // slot is filled; latecomers find the counter exhausted and leave.
-constexpr uint32_t kStreamGrid = 1024;
+#ifndef DEFT_STREAM_GRID
+#define DEFT_STREAM_GRID 1024
+#endif
+constexpr uint32_t kStreamGrid = DEFT_STREAM_GRID;
 // Workgroups of the grid-stride third-level kernel of long vectors (measured on 1.42 GB: 24 / 17 /
 // 15 / 12.8 / 13 us with 512 / 768 / 1024 / 1536 / 2048).
 constexpr uint32_t kSlotWaveGrid = 2048;
@@ -244,7 +247,30 @@ struct SegDesc {
   uint32_t out_off;     // first output slot of the segment
   uint32_t chunk_base;  // first chunk id of the segment in the count/emit passes
   uint32_t hchunk_base; // first chunk id of the segment in the histogram passes (larger chunks)
+  uint32_t sblock_base; // first workgroup of the segment in the sampling kernel (long vectors)
+  uint32_t sampled;     // 0, or 1 + the number of the segment's bounded histogram: the segment is
+                        // sampled ahead of its first pass (long vectors)
 };
+
+// How the first pass treats a segment of a long vector.
+//   kModeFull:    top-digit histogram of every key, nothing parked (pass 2 parks).
+//   kModeBounded: a sample of the segment has placed the threshold's top digit in
+//                 b_lo .. b_lo + 3; the first pass parks every key whose top digit is at least
+//                 b_lo and histograms the keys of those four digits on their top 21 bits (4096 bins
+//                 of 2^10 keys), so that the segment is read once.  Checked exactly afterwards
+//                 (find_first_kernel).
+//   kModeFailed:  the check failed (the sample misled): the segment is read again as kModeFull.
+constexpr uint32_t kModeFull = 0, kModeBounded = 1, kModeFailed = 2;
+constexpr int kHiCopies = 16;
+struct SegBound {
+  uint32_t mode;
+  uint32_t b_lo;
+  uint32_t pad[2];
+  uint32_t hi[kHiCopies];  // keys above the four digits, counted by the first pass (copies as for the
+                           // histograms: workgroup b adds to hi[b % kHiCopies])
+};
+// Bits of the flag word the first bucket search leaves for the kernels behind it.
+constexpr uint32_t kFlagPass2 = 2u;  // some segment needs the full first pass and pass 2
 
 struct SegState {
   uint32_t prefix;  // key bits fixed so far (right-aligned)
@@ -255,14 +281,14 @@ struct SegState {
   uint32_t pad[3];
 };
 
-constexpr int kSegBatch = 160;
+constexpr int kSegBatch = 120;
 struct SegBatch {
   int32_t first;
   int32_t count;
   uint32_t total_chunks;  // written as the sentinel chunk_base of segment m by the last batch
   uint32_t total_hchunks;
   int32_t m;
-  int32_t pad;
+  uint32_t total_sblocks;
   SegDesc d[kSegBatch];
 };
 static_assert(sizeof(SegBatch) <= 4000, "kernel argument block too large");
@@ -272,9 +298,16 @@ constexpr int kBits0 = 11, kBits1 = 10, kBits2 = 10;
 // Run by one workgroup: stores a batch of segment descriptors (passed as kernel arguments) and
 // their initial state; the last batch adds the sentinel descriptor that closes the chunk ranges.
 __device__ __forceinline__ void store_segments(const SegBatch& b, SegDesc* __restrict__ seg,
-                                               SegState* __restrict__ st) {
+                                               SegState* __restrict__ st,
+                                               SegBound* __restrict__ bnd = nullptr) {
   for (int i = threadIdx.x; i < b.count; i += kThreads) {
     seg[b.first + i] = b.d[i];
+    if (bnd) {
+      SegBound z;
+      z.mode = kModeFull; z.b_lo = 0; z.pad[0] = z.pad[1] = 0;
+      for (int q = 0; q < kHiCopies; ++q) z.hi[q] = 0;
+      bnd[b.first + i] = z;
+    }
     SegState s;
     s.prefix = 0; s.k_rem = b.d[i].k; s.T = 0; s.r = 0; s.done = 0;
     s.pad[0] = s.pad[1] = s.pad[2] = 0;
@@ -282,7 +315,7 @@ __device__ __forceinline__ void store_segments(const SegBatch& b, SegDesc* __res
   }
   if (threadIdx.x == 0 && b.first + b.count == b.m) {
     SegDesc z; z.start = 0; z.size = 0; z.k = 0; z.out_off = 0; z.chunk_base = b.total_chunks;
-    z.hchunk_base = b.total_hchunks;
+    z.hchunk_base = b.total_hchunks; z.sblock_base = b.total_sblocks; z.sampled = 0;
     seg[b.m] = z;
   }
 }
@@ -291,14 +324,17 @@ __device__ __forceinline__ void store_segments(const SegBatch& b, SegDesc* __res
 // clears the histograms.
 __global__ __launch_bounds__(kThreads) void seg_setup_kernel(SegBatch b, SegDesc* __restrict__ seg,
                                                              SegState* __restrict__ st,
+                                                             SegBound* __restrict__ bnd,
+                                                             uint32_t* __restrict__ stats,
                                                              uint32_t* __restrict__ zero_from,
                                                              size_t zero_count) {
+  if (b.first == 0 && blockIdx.x == 0 && threadIdx.x < DEFT_STAT_WORDS) stats[threadIdx.x] = 0;
   if (b.first == 0) {
     for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < zero_count;
          i += (size_t)gridDim.x * kThreads)
       zero_from[i] = 0u;
   }
-  if (blockIdx.x == 0) store_segments(b, seg, st);
+  if (blockIdx.x == 0) store_segments(b, seg, st, bnd);
 }
 
 // Clears the histogram area ahead of time (while the host still plans), for the selection that
@@ -421,10 +457,25 @@ __host__ __device__ inline uint32_t chunks_of(uint32_t start, uint32_t size, uin
 #endif
 constexpr int kRep0 = DEFT_HIST0_COPIES;
 constexpr int kRep12 = DEFT_HIST12_COPIES;
-__host__ __device__ constexpr int hist_copies(int level) { return level == 0 ? kRep0 : kRep12; }
+// Level 3 is not a fourth digit: it names the 4096-bin histogram that the first pass of a
+// sampled long-vector segment builds over the four top digits around the threshold (12 bits of
+// 2^10 keys each), which then stands for levels 0 and 1 together.  It has storage of its own, in
+// kRepB copies: with rounded gradients every workgroup that parks anything adds to the same few
+// dozen bins, and with three copies those merges cost 10 us of a 216 us pass over 1.42 GB.
+// A launch gives at most kMaxSampled segments such a histogram (it samples no more than that).
+constexpr int kBitsB = 12;
+#ifndef DEFT_BOUNDED_COPIES
+#define DEFT_BOUNDED_COPIES 8
+#endif
+constexpr int kRepB = DEFT_BOUNDED_COPIES;
+constexpr int kBoundedStride = (1 << kBitsB) * kRepB;
+constexpr int kMaxSampled = 64;
+__host__ __device__ constexpr int hist_copies(int level) {
+  return level == 0 ? kRep0 : (level == 3 ? kRepB : kRep12);
+}
 constexpr int kHistStride = (1 << kBits0) * kRep0 + ((1 << kBits1) + (1 << kBits2)) * kRep12;
 __host__ __device__ constexpr int hist_offset(int level) {
-  return level == 0 ? 0
+  return (level == 0 || level == 3) ? 0
                     : (level == 1 ? (1 << kBits0) * kRep0 : (1 << kBits0) * kRep0 + (1 << kBits1) * kRep12);
 }
 
@@ -437,7 +488,7 @@ __host__ __device__ constexpr int hist_offset(int level) {
 // bins just below kBins - t*kPer, i.e. threads walk the buckets from the largest keys down.
 template <int LEVEL>
 struct LevelBins {
-  static constexpr int kBits = LEVEL == 0 ? kBits0 : (LEVEL == 1 ? kBits1 : kBits2);
+  static constexpr int kBits = LEVEL == 0 ? kBits0 : (LEVEL == 1 ? kBits1 : (LEVEL == 2 ? kBits2 : kBitsB));
   static constexpr int kBins = 1 << kBits;
   static constexpr int kPer = kBins / kThreads;
   uint32_t v[kPer];
@@ -457,8 +508,8 @@ struct LevelBins {
 template <int LEVEL>
 __device__ __forceinline__ SegState find_bucket(const LevelBins<LEVEL>& bins, SegState s,
                                                 uint32_t* __restrict__ lds /* kWaves + 8 words */) {
-  constexpr int kBits = LEVEL == 0 ? kBits0 : (LEVEL == 1 ? kBits1 : kBits2);
-  constexpr int kRemBits = LEVEL == 0 ? (kBits1 + kBits2) : (LEVEL == 1 ? kBits2 : 0);
+  constexpr int kBits = LevelBins<LEVEL>::kBits;
+  constexpr int kRemBits = LEVEL == 0 ? (kBits1 + kBits2) : ((LEVEL == 1 || LEVEL == 3) ? kBits2 : 0);
   constexpr int kBins = 1 << kBits;
   constexpr int kPer = kBins / kThreads;
   const int top = kBins - threadIdx.x * kPer;
@@ -616,6 +667,185 @@ __global__ __launch_bounds__(kThreads) void hist0_inline_kernel(const float* __r
   hist0_chunk<HITERS>(g, d, lo, hist, hmax);
 }
 
+// ------------------------------------------------------------------------------------------
+// Long vectors: a sample places the threshold ahead of the first pass
+// ------------------------------------------------------------------------------------------
+// One piece of kSamplePiece consecutive elements out of every block of kSampleBlock (1/128 of the
+// segment), at a position inside the block that changes pseudo-randomly from block to block so
+// that rows or columns of a matrix cannot line up with it.  A workgroup takes kSamplePiecesPerWg
+// pieces (eight lanes per piece, one 16-byte load each, all loads in flight together) and
+// histograms their keys on the top digit.
+constexpr int kSampleBlock = 4096;
+constexpr int kSamplePiece = 32;
+constexpr int kSampleRows = 16;
+constexpr int kSamplePiecesPerWg = (kThreads / 8) * kSampleRows;
+constexpr int kSampleCopies = 2;  // copies of a segment's sample histogram
+// A sampled count X of a class holding C of the segment's elements is near p*C with standard
+// deviation at most sqrt(p*C) (p = sampled fraction).  The bounds below sit kSampleZ such
+// deviations away from p*k; a sample that still misleads is caught by the exact check after the
+// first pass, so this number trades speed, never results.
+constexpr double kSampleZ = 8.0;
+
+__host__ __device__ inline uint32_t sample_pieces(uint32_t start, uint32_t size) {
+  const uint64_t a = ((uint64_t)start + 3) & ~uint64_t(3);
+  const uint64_t e = (uint64_t)start + size;
+  return e > a ? (uint32_t)((e - a) / kSampleBlock) : 0u;
+}
+
+__device__ __forceinline__ int seg_of_sblock(const SegDesc* __restrict__ seg, int m, uint32_t c) {
+  int lo = 0, hi = m;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (seg[mid].sblock_base <= c) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// The sample histogram of a segment borrows the storage of its level-1 and level-2 histograms
+// (kSampleCopies x 2048 words = their combined size); bounds_kernel clears it again.
+static_assert(kSampleCopies * (1 << kBits0) == ((1 << kBits1) + (1 << kBits2)) * kRep12,
+              "the sample histogram must fit the level-1/2 area exactly");
+
+__global__ __launch_bounds__(kThreads) void sample_hist_kernel(const float* __restrict__ g,
+                                                               const SegDesc* __restrict__ seg, int m,
+                                                               uint32_t* __restrict__ hist) {
+  constexpr int kBins = 1 << kBits0;
+  constexpr int kShift = kBits1 + kBits2;
+  __shared__ uint32_t lh[kBins];
+  for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
+  const int j = seg_of_sblock(seg, m, blockIdx.x);
+  const SegDesc d = seg[j];
+  const uint32_t pieces = sample_pieces(d.start, d.size);
+  const uint64_t a = ((uint64_t)d.start + 3) & ~uint64_t(3);
+  const uint32_t first = (blockIdx.x - d.sblock_base) * kSamplePiecesPerWg + (threadIdx.x >> 3);
+  v4u v[kSampleRows];
+  uint32_t have = 0;
+#pragma unroll
+  for (int r = 0; r < kSampleRows; ++r) {
+    const uint32_t q = first + r * (kThreads / 8);
+    v[r] = v4u{0u, 0u, 0u, 0u};
+    if (q < pieces) {
+      const uint32_t off = ((q * 2654435761u) >> 25) & (kSampleBlock / kSamplePiece - 1);
+      const uint64_t at = a + (uint64_t)q * kSampleBlock + off * kSamplePiece + (threadIdx.x & 7) * 4;
+      v[r] = *reinterpret_cast<const v4u*>(g + at);
+      have |= 1u << r;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < kSampleRows; ++r) {
+    if ((have >> r) & 1u) {
+      atomicAdd(&lh[(v[r].x & 0x7FFFFFFFu) >> kShift], 1u);
+      atomicAdd(&lh[(v[r].y & 0x7FFFFFFFu) >> kShift], 1u);
+      atomicAdd(&lh[(v[r].z & 0x7FFFFFFFu) >> kShift], 1u);
+      atomicAdd(&lh[(v[r].w & 0x7FFFFFFFu) >> kShift], 1u);
+    }
+  }
+  __syncthreads();
+  uint32_t* gh = hist + (size_t)j * kHistStride + hist_offset(1) + (blockIdx.x % kSampleCopies) * kBins;
+  for (int b = threadIdx.x; b < kBins; b += kThreads) {
+    const uint32_t c = lh[b];
+    if (c) atomicAdd(&gh[b], c);
+  }
+}
+
+// Largest bin b whose count of keys at or above it reaches `thr` (thr >= 1), given each thread's
+// bins and the count above them; written to *out by the one thread that holds it, together with
+// that count.  Nothing is written if the whole histogram holds fewer than thr keys.
+__device__ __forceinline__ void crossing_bin(const LevelBins<0>& bins, uint32_t before, uint32_t thr,
+                                             uint32_t* out) {
+  constexpr int kPer = LevelBins<0>::kPer;
+  const int top = LevelBins<0>::kBins - threadIdx.x * kPer;
+  uint32_t above = before;
+#pragma unroll
+  for (int q = 0; q < kPer; ++q) {
+    if (above < thr && thr <= above + bins.v[q]) { out[0] = (uint32_t)(top - 1 - q); out[1] = above + bins.v[q]; }
+    above += bins.v[q];
+  }
+}
+
+// One workgroup per segment: from the sample histogram, the top digit b_lo such that the
+// threshold's top digit is one of b_lo .. b_lo + 3 beyond reasonable doubt -- or the decision to treat
+// the segment in full (not sampled, too few samples to tell, the sample's doubt spanning more
+// than four digits, or too many keys at or above b_lo to park).
+__global__ __launch_bounds__(kThreads) void bounds_kernel(const SegDesc* __restrict__ seg,
+                                                          uint32_t* __restrict__ hist,
+                                                          SegBound* __restrict__ bnd,
+                                                          uint32_t* __restrict__ flags) {
+  __shared__ uint32_t wsum[kWaves];
+  __shared__ uint32_t res[4];
+  const int j = blockIdx.x;
+  const SegDesc d = seg[j];
+  if (!d.sampled) {  // bnd[j] already says kModeFull
+    if (threadIdx.x == 0) atomicOr(flags, kFlagPass2);
+    return;
+  }
+  uint32_t* gh = hist + (size_t)j * kHistStride + hist_offset(1);
+  LevelBins<0> bins;
+  {
+    constexpr int kPer = LevelBins<0>::kPer;
+    const int top = LevelBins<0>::kBins - threadIdx.x * kPer;
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) {
+      uint32_t c = 0;
+#pragma unroll
+      for (int r = 0; r < kSampleCopies; ++r) {
+        c += gh[r * LevelBins<0>::kBins + top - 1 - q];
+        gh[r * LevelBins<0>::kBins + top - 1 - q] = 0;  // hand the area back cleared
+      }
+      bins.v[q] = c;
+    }
+  }
+  uint32_t mine = 0;
+#pragma unroll
+  for (int q = 0; q < LevelBins<0>::kPer; ++q) mine += bins.v[q];
+  uint32_t inc = mine;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t n = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += n;
+  }
+  if (lane == 63) wsum[wave] = inc;
+  if (threadIdx.x == 0) { res[0] = 0; res[1] = 0; res[2] = 0xFFFFFFFFu; res[3] = 0; }
+  __syncthreads();
+  uint32_t before = inc - mine;
+  for (int w = 0; w < wave; ++w) before += wsum[w];
+  const uint32_t n_s = sample_pieces(d.start, d.size) * kSamplePiece;
+  const double pk = (double)d.k * (double)n_s / (double)d.size;
+  const double dev = kSampleZ * sqrt(pk) + 1.0;
+  const uint32_t hi_thr = (uint32_t)ceil(pk + dev);
+  const double lo_real = pk - dev;
+  const uint32_t lo_thr = lo_real >= 0.0 ? (uint32_t)floor(lo_real) + 1u : 0u;
+  // b_lo: keys at or above it number at least k beyond doubt.  b_hi: keys above it number fewer
+  // than k beyond doubt.
+  if (hi_thr <= n_s) crossing_bin(bins, before, hi_thr, &res[0]);
+  if (lo_thr >= 1) crossing_bin(bins, before, lo_thr, &res[2]);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const uint32_t b_lo = res[0], at_or_above = res[1], b_hi = res[2];
+    const bool ok = hi_thr <= n_s && lo_thr >= 1 && b_hi != 0xFFFFFFFFu && b_hi <= b_lo + 3 &&
+                    (uint64_t)at_or_above * 32u <= n_s;  // parks about 3 % of the segment at most
+    bnd[j].mode = ok ? kModeBounded : kModeFull;
+    bnd[j].b_lo = b_lo;
+    if (!ok) atomicOr(flags, kFlagPass2);
+  }
+}
+
+// Pass 1 for long vectors.  Merging a workgroup's histogram into the segment's costs one
+// device-scope atomic per occupied bin; with one chunk per workgroup that merge took a quarter
+// of the pass on a 1.4 GB vector (281 us; 211 us with the merge left out, 238 / 219 us when
+// only every 4th / 20th workgroup merged).  Here a resident set of workgroups draws chunks from
+// a counter (the next draw is issued before the current chunk is processed) and keeps
+// accumulating in LDS; a workgroup merges when its next chunk belongs to another segment and
+// when the chunks run out.  The counter only grows, so every workgroup leaves its loop.
+//   kModeFull segments: histogram of the top digit of every key, largest top digit per chunk.
+//   kModeBounded segments: keys whose top digit is at least b_lo are parked as in pass 2 (one
+//     wavefront per count/emit chunk, index order) and, where the digit is one of b_lo .. b_lo + 3,
+//     histogrammed on (key - (b_lo << 20)) >> 10, i.e. on their top 21 bits; keys above those four
+//     digits are counted.  Nearly every step finds nothing to park: four compares and a ballot.
+//   REDO launch: only the segments whose bound failed its check, treated as kModeFull; a no-op
+//     (every workgroup leaves at once) unless the flag word says that some bound failed.
 // Pass 1 for long vectors.  Merging a workgroup's histogram into the segment's costs one
 // device-scope atomic per occupied bin; with one chunk per workgroup that merge took a quarter
 // of the pass on a 1.4 GB vector (281 us; 211 us with the merge left out, 238 / 219 us when
@@ -624,14 +854,18 @@ __global__ __launch_bounds__(kThreads) void hist0_inline_kernel(const float* __r
 // accumulating in LDS; a workgroup merges when its next chunk belongs to another segment and
 // when the chunks run out.  The counter only grows, so every workgroup leaves its loop.  The
 // largest top digit of each chunk comes from the keys (the LDS histogram now spans chunks).
+// With `bnd` (some segment of the launch was sampled) the pass covers only the segments that are
+// not, or no longer, kModeBounded, and is a no-op unless the flag word says there are any.
 template <int HITERS>
 __global__ __launch_bounds__(kThreads) void hist0_stream_kernel(
     const float* __restrict__ g, const SegDesc* __restrict__ seg, int m, uint32_t hchunks,
-    uint32_t* __restrict__ hist, uint32_t* __restrict__ hmax, uint32_t* __restrict__ next_chunk) {
+    uint32_t* __restrict__ hist, uint32_t* __restrict__ hmax, uint32_t* __restrict__ next_chunk,
+    const SegBound* __restrict__ bnd, const uint32_t* __restrict__ flags) {
   constexpr int kBins = 1 << kBits0;
   constexpr int kShift = kBits1 + kBits2;
   __shared__ uint32_t lh[kBins];
   __shared__ uint32_t draw[2];
+  if (bnd && !(*flags & kFlagPass2)) return;
   for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
   if (threadIdx.x == 0) draw[0] = atomicAdd(next_chunk, 1u);
   __syncthreads();
@@ -640,6 +874,12 @@ __global__ __launch_bounds__(kThreads) void hist0_stream_kernel(
   while (c < hchunks) {
     if (threadIdx.x == 0) draw[turn ^ 1] = atomicAdd(next_chunk, 1u);
     const int j = seg_of_hchunk(seg, m, c);
+    if (bnd && bnd[j].mode == kModeBounded) {  // read once already, candidates parked
+      __syncthreads();
+      turn ^= 1;
+      c = draw[turn];
+      continue;
+    }
     if (j != cur) {
       if (cur >= 0) {
         uint32_t* gh = hist + (size_t)cur * kHistStride + hist_offset(0) + (blockIdx.x % kRep0) * kBins;
@@ -688,6 +928,209 @@ __global__ __launch_bounds__(kThreads) void hist0_stream_kernel(
   }
 }
 
+// The first pass over the kModeBounded segments of a long vector: one workgroup per histogram
+// chunk, one wavefront per count/emit chunk.  Keys whose top digit is at least b_lo are parked as
+// in pass 2 (index order) and, where the digit is one of b_lo .. b_lo + 3, histogrammed on
+// (key - (b_lo << 20)) >> 10, i.e. on their top 21 bits; keys above those four digits are
+// counted.  Nearly every step finds nothing to park: four compares and a ballot.
+// A wavefront walks its 8192 elements in batches of kBatchVecs 16-byte vectors per lane, the next
+// batch in flight while the current one is processed, in a loop that is kept rolled: the pass
+// needs few registers (a chunk held whole, 32 vectors per lane, costs 256 and leaves one
+// wavefront per SIMD: 310 us on 1.42 GB), so that many wavefronts per SIMD keep loads in flight.
+#ifndef DEFT_PASS1_BATCH
+#define DEFT_PASS1_BATCH 32
+#endif
+#ifndef DEFT_PASS1_DOUBLE
+#define DEFT_PASS1_DOUBLE 0
+#endif
+constexpr int kBatchVecs = DEFT_PASS1_BATCH;
+constexpr bool kBatchDouble = DEFT_PASS1_DOUBLE != 0;
+
+struct VecBatch {
+  v4u v[kBatchVecs];
+  uint32_t valid[(kBatchVecs + 7) / 8];  // 4 bits per vector: which components lie inside the segment
+  __device__ __forceinline__ uint32_t vmask(int i) const { return (valid[i >> 3] >> ((i & 7) * 4)) & 0xFu; }
+};
+
+// Loads vectors t0 .. t0 + kBatchVecs - 1 of this lane (vector t sits 256 * t elements behind
+// `at`, the lane's first).  INTERIOR: the whole chunk lies inside [s, e).
+template <bool INTERIOR>
+__device__ __forceinline__ void load_batch(VecBatch& b, const float* __restrict__ g, int64_t at, int t0,
+                                           int64_t s, int64_t e) {
+  if (INTERIOR) {
+    const v4u* __restrict__ p = reinterpret_cast<const v4u*>(g + at);
+#pragma unroll
+    for (int i = 0; i < kBatchVecs; ++i) b.v[i] = __builtin_nontemporal_load(&p[(t0 + i) * 64]);
+    return;
+  }
+#pragma unroll
+  for (int w = 0; w < (kBatchVecs + 7) / 8; ++w) b.valid[w] = 0;
+#pragma unroll
+  for (int i = 0; i < kBatchVecs; ++i) {
+    const int64_t p = at + (int64_t)(t0 + i) * 256;
+    uint32_t x[4] = {0u, 0u, 0u, 0u};
+    if (p >= s && p + 4 <= e) {
+      const uint4 w = *reinterpret_cast<const uint4*>(g + p);
+      x[0] = w.x; x[1] = w.y; x[2] = w.z; x[3] = w.w;
+      b.valid[i >> 3] |= 0xFu << ((i & 7) * 4);
+    } else {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        if (p + c >= s && p + c < e) {
+          x[c] = __float_as_uint(g[p + c]);
+          b.valid[i >> 3] |= 1u << ((i & 7) * 4 + c);
+        }
+      }
+    }
+    b.v[i] = v4u{x[0], x[1], x[2], x[3]};
+  }
+}
+
+// The walk of one wavefront over its count/emit chunk.  The common step finds nothing to park
+// (four compares and a ballot); the next most common finds at most one key per lane (one ballot
+// places them); only a step in which some lane holds several takes the general three-ballot
+// prefix.  Parked entries go to a staging array in LDS first and leave it at the end of the walk,
+// 64 at a time: dense stores to the chunk's slots, and the histogram update with every lane busy
+// instead of once per sparse step.  The instruction count of the sparse steps is what bounds the
+// pass once the candidates are a few per cent of the keys (a wavefront instruction occupies its
+// SIMD for four cycles, which at full memory rate leaves about twenty of them per element on the
+// whole chip).
+constexpr uint32_t kStageCap = 2 * kMaxSlotCap;  // the slot capacity of the long-vector shape
+template <int HITERS, bool INTERIOR>
+__device__ __forceinline__ uint32_t park_chunk(const float* __restrict__ g, int64_t at, int64_t s,
+                                               int64_t e, uint32_t lo_key, uint32_t* __restrict__ lh,
+                                               uint2* __restrict__ stage, uint2* __restrict__ my_slots) {
+  constexpr int kBinsB = 1 << kBitsB;
+  constexpr int kShift = kBits1 + kBits2;
+  constexpr int kBatches = HITERS / kBatchVecs;
+  const int lane = threadIdx.x & 63;
+  const unsigned long long below = (1ull << lane) - 1ull;
+  uint32_t filled = 0;
+  auto bin_of = [&](uint32_t rawv) {
+    const uint32_t rel = (rawv & 0x7FFFFFFFu) - lo_key;
+    return rel < (4u << kShift) ? (rel >> kBits2) : (uint32_t)kBinsB;
+  };
+  auto one = [&](uint32_t rawv, uint32_t idx, uint32_t pos) {
+    if (pos < kStageCap) stage[pos] = make_uint2(rawv, idx);
+    else atomicAdd(&lh[bin_of(rawv)], 1u);  // beyond the slots: counted, not kept
+  };
+  auto park = [&](const VecBatch& B, int t0) {
+#pragma unroll
+    for (int i = 0; i < kBatchVecs; ++i) {
+      const uint32_t vm = INTERIOR ? 0xFu : B.vmask(i);
+      const uint32_t raw[4] = {B.v[i].x, B.v[i].y, B.v[i].z, B.v[i].w};
+      bool l[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) l[q] = ((vm >> q) & 1u) && (raw[q] & 0x7FFFFFFFu) >= lo_key;
+      const bool any = l[0] || l[1] || l[2] || l[3];
+      const unsigned long long anyb = __ballot(any);
+      if (anyb == 0ull) continue;
+      const uint32_t idx0 = (uint32_t)(at + (int64_t)(t0 + i) * 256);
+      const uint32_t cnt = (uint32_t)l[0] + (uint32_t)l[1] + (uint32_t)l[2] + (uint32_t)l[3];
+      if (__ballot(cnt > 1u) == 0ull) {
+        // at most one key per lane: its slot is the number of lanes with a key below this one
+        if (any) {
+          const uint32_t comp = l[0] ? 0u : (l[1] ? 1u : (l[2] ? 2u : 3u));
+          const uint32_t rawv = l[0] ? raw[0] : (l[1] ? raw[1] : (l[2] ? raw[2] : raw[3]));
+          one(rawv, idx0 + comp, filled + (uint32_t)__popcll(anyb & below));
+        }
+        filled += (uint32_t)__popcll(anyb);
+        continue;
+      }
+      uint32_t tot;
+      uint32_t pos = filled + wave_excl_small(cnt, tot);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (l[q]) {
+          one(raw[q], idx0 + q, pos);
+          ++pos;
+        }
+      }
+      filled += tot;
+    }
+  };
+  VecBatch bufA;
+  load_batch<INTERIOR>(bufA, g, at, 0, s, e);
+  __syncthreads();  // the workgroup's histogram is cleared
+  if (kBatchDouble) {
+    // two batches in turn: one being processed, the other in flight
+    VecBatch bufB;
+#pragma unroll 1
+    for (int bt = 0; bt < kBatches; bt += 2) {
+      load_batch<INTERIOR>(bufB, g, at, (bt + 1) * kBatchVecs, s, e);
+      park(bufA, bt * kBatchVecs);
+      if (bt + 2 < kBatches) load_batch<INTERIOR>(bufA, g, at, (bt + 2) * kBatchVecs, s, e);
+      park(bufB, (bt + 1) * kBatchVecs);
+    }
+  } else {
+#pragma unroll 1
+    for (int bt = 0; bt < kBatches; ++bt) {
+      if (bt) load_batch<INTERIOR>(bufA, g, at, bt * kBatchVecs, s, e);
+      park(bufA, bt * kBatchVecs);
+    }
+  }
+  // the staged entries (written and read by this wavefront only) leave for the slots
+  const uint32_t kept = min(filled, kStageCap);
+  for (uint32_t r = lane; r < kept; r += 64) {
+    const uint2 en = stage[r];
+    my_slots[r] = en;
+    atomicAdd(&lh[bin_of(en.x)], 1u);
+  }
+  return filled;
+}
+
+template <int HITERS>
+__global__ __launch_bounds__(kThreads) void pass1_bounded_kernel(
+    const float* __restrict__ g, const SegDesc* __restrict__ seg, int m, uint32_t* __restrict__ bhist,
+    SegBound* __restrict__ bnd, uint32_t* __restrict__ live_cnt, uint2* __restrict__ slots,
+    uint32_t cap) {
+  constexpr int kBinsB = 1 << kBitsB;
+  constexpr int kShift = kBits1 + kBits2;
+  static_assert(HITERS % kBatchVecs == 0 && (!kBatchDouble || HITERS % (2 * kBatchVecs) == 0),
+                "a wavefront's vectors split into whole batches (pairs of them when double-buffered)");
+  constexpr int kElems = kThreads * 4 * HITERS;  // elements of a histogram chunk
+  // kBinsB bins over the four digits, the count of the keys above them in [kBinsB], and in
+  // [kBinsB + 1] whether this workgroup has parked anything at all
+  __shared__ uint32_t lh[kBinsB + 2];
+  __shared__ uint2 stage[kWaves][kStageCap];
+  const int j = seg_of_hchunk(seg, m, blockIdx.x);
+  if (bnd[j].mode != kModeBounded) return;
+  for (int b = threadIdx.x; b < kBinsB + 2; b += kThreads) lh[b] = 0;
+  const SegDesc d = seg[j];
+#ifdef DEFT_PROBE_NOPARK  // measurement only: nothing is ever parked (the check then fails: redone in full)
+  const uint32_t lo_key = (bnd[j].b_lo << kShift) | 0x7FF00000u;
+#else
+  const uint32_t lo_key = bnd[j].b_lo << kShift;
+#endif
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t local = blockIdx.x - d.hchunk_base;
+  const int64_t s = d.start, e = (int64_t)d.start + d.size;
+  const int64_t cstart = (s & ~int64_t(3)) + (int64_t)local * kElems;
+  // this lane's first vector: wave w owns the w-th quarter of the chunk
+  const int64_t at = cstart + ((int64_t)wave * HITERS * 64 + lane) * 4;
+  const uint32_t n_chunks = seg[j + 1].chunk_base - d.chunk_base;
+  const uint32_t ec_local = local * 4 + wave;  // this wave's count/emit chunk
+  uint2* my_slots = slots + (size_t)(d.chunk_base + ec_local) * cap;
+  const uint32_t filled = (cstart >= s && cstart + kElems <= e)
+                              ? park_chunk<HITERS, true>(g, at, s, e, lo_key, lh, stage[wave], my_slots)
+                              : park_chunk<HITERS, false>(g, at, s, e, lo_key, lh, stage[wave], my_slots);
+  if (lane == 0) {
+    if (ec_local < n_chunks) live_cnt[d.chunk_base + ec_local] = filled;
+    if (filled) lh[kBinsB + 1] = 1u;
+  }
+  __syncthreads();
+  if (!lh[kBinsB + 1]) return;  // nothing parked (the common case in layers of small magnitude)
+#ifdef DEFT_PROBE_NOMERGE  // measurement only: the check then fails and the segment is redone in full
+  if (lo_key) return;
+#endif
+  uint32_t* gh = bhist + (size_t)(d.sampled - 1) * kBoundedStride + (blockIdx.x % kRepB) * kBinsB;
+  for (int b = threadIdx.x; b < kBinsB; b += kThreads) {
+    const uint32_t v = lh[b];
+    if (v) atomicAdd(&gh[b], v);
+  }
+  if (threadIdx.x == 0 && lh[kBinsB]) atomicAdd(&bnd[j].hi[blockIdx.x % kHiCopies], lh[kBinsB]);
+}
+
 // Pass 2 (the second, partial read).  The top digit b0 of the threshold is known.  Every key that can
 // still be selected -- top digit above b0 (selected for sure) or equal to b0 ("candidates"; the
 // two together are about as many as k) -- is parked with its index in a small per-chunk slot
@@ -701,12 +1144,16 @@ template <int ITERS, bool FUSED>
 __global__ __launch_bounds__(kThreads) void pass2_kernel(
     const float* __restrict__ g, const SegDesc* __restrict__ seg, SegState* __restrict__ st, int m,
     uint32_t* __restrict__ hist, const uint32_t* __restrict__ hmax, uint32_t* __restrict__ live_cnt,
-    uint2* __restrict__ slots, uint32_t cap) {
+    uint2* __restrict__ slots, uint32_t cap, const SegBound* __restrict__ bnd,
+    const uint32_t* __restrict__ flags) {
   constexpr int HITERS = 4 * ITERS;
   constexpr int kBins = 1 << kBits1;
   __shared__ uint32_t lh[kBins];
   __shared__ uint32_t fl[kWaves + 8];
+  // long vectors: nothing to do if the first pass has parked every segment's candidates itself
+  if (!FUSED && bnd && !(*flags & kFlagPass2)) return;
   const int j = seg_of_hchunk(seg, m, blockIdx.x);
+  if (!FUSED && bnd && bnd[j].mode == kModeBounded) return;
   const SegDesc d = seg[j];
   const uint32_t local = blockIdx.x - d.hchunk_base;
   const uint32_t my_max = hmax[blockIdx.x];  // fetched ahead of the bucket search
@@ -818,14 +1265,72 @@ __global__ __launch_bounds__(kThreads) void slot_hist2_kernel(
 // unfused form of the hand-over).
 template <int LEVEL>
 __global__ __launch_bounds__(kThreads) void find_kernel(SegState* __restrict__ st, int m,
-                                                        const uint32_t* __restrict__ hist) {
+                                                        const uint32_t* __restrict__ hist,
+                                                        const SegBound* __restrict__ bnd) {
   __shared__ uint32_t fl[kWaves + 8];
   const int j = blockIdx.x;
+  // a segment whose first pass covered two digit levels already has its state after level 1
+  if (LEVEL <= 1 && bnd && bnd[j].mode == kModeBounded) return;
   SegState s = st[(size_t)LEVEL * m + j];
   LevelBins<LEVEL> bins;
   bins.load(hist + (size_t)j * kHistStride + hist_offset(LEVEL));
   if (!s.done) s = find_bucket<LEVEL>(bins, s, fl);
   if (threadIdx.x == 0) st[(size_t)(LEVEL + 1) * m + j] = s;
+}
+
+// The exact check behind the first pass over kModeBounded segments, one workgroup per segment:
+// with c_hi keys above the four digits and c_mid keys inside them, the threshold lies inside iff
+// c_hi < k <= c_hi + c_mid.  If so, the bucket search over the 4096-bin histogram gives the state
+// after TWO digit levels (the full first pass, pass 2 and the searches of levels 0 and 1 then
+// skip the segment).  If not -- the sample misled -- the segment is marked kModeFailed and the
+// launches that follow treat it in full.
+__global__ __launch_bounds__(kThreads) void find_first_kernel(SegState* __restrict__ st, int m,
+                                                              const SegDesc* __restrict__ seg,
+                                                              const uint32_t* __restrict__ bhist,
+                                                              SegBound* __restrict__ bnd,
+                                                              uint32_t* __restrict__ flags,
+                                                              uint32_t* __restrict__ stats) {
+  __shared__ uint32_t fl[kWaves + 8];
+  __shared__ uint32_t wsum[kWaves];
+  const int j = blockIdx.x;
+  if (bnd[j].mode != kModeBounded) {
+    if (threadIdx.x == 0) atomicAdd(&stats[DEFT_STAT_FULL], 1u);
+    return;
+  }
+  const SegState s = st[j];
+  LevelBins<3> bins;
+  bins.load(bhist + (size_t)(seg[j].sampled - 1) * kBoundedStride);
+  uint32_t mid = 0;
+#pragma unroll
+  for (int q = 0; q < LevelBins<3>::kPer; ++q) mid += bins.v[q];
+  mid = wave_sum_u32(mid);
+  if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = mid;
+  __syncthreads();
+  const uint32_t c_mid = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+  uint32_t c_hi = 0;
+  for (int q = 0; q < kHiCopies; ++q) c_hi += bnd[j].hi[q];
+  const uint32_t k = s.k_rem;
+  if (c_hi < k && (uint64_t)k <= (uint64_t)c_hi + c_mid) {
+    SegState t = s;
+    t.prefix = 0;
+    t.k_rem = k - c_hi;
+    t = find_bucket<3>(bins, t, fl);  // t.prefix: the bin, i.e. the key's top 21 bits less b_lo << 10
+    SegState o = s;
+    o.prefix = (bnd[j].b_lo << kBits1) + t.prefix;
+    o.k_rem = t.k_rem;
+    o.done = t.done;
+    o.T = t.done ? (o.prefix << kBits2) : 0u;  // the whole bucket is taken
+    o.r = t.done ? 0xFFFFFFFFu : 0u;
+    if (threadIdx.x == 0) {
+      st[(size_t)m + j] = o;
+      st[(size_t)2 * m + j] = o;
+      atomicAdd(&stats[DEFT_STAT_BOUNDED], 1u);
+    }
+  } else if (threadIdx.x == 0) {
+    bnd[j].mode = kModeFailed;
+    atomicOr(flags, kFlagPass2);
+    atomicAdd(&stats[DEFT_STAT_REDONE], 1u);
+  }
 }
 
 // Per count/emit chunk: how many keys exceed T and how many equal it -- from the slots of
@@ -1389,14 +1894,28 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // Vectors above this many elements use the long-vector launch shape (larger chunks, separate
 // bucket-search kernels, wave-per-chunk slot kernels) unless the caller names a shape.
 constexpr int64_t kLongVectorElems = int64_t(1) << 25;
-inline bool valid_shape(int32_t shape) { return shape >= DEFT_SHAPE_AUTO && shape <= DEFT_SHAPE_LONG; }
+inline bool valid_shape(int32_t shape) {
+  return shape >= DEFT_SHAPE_AUTO && shape <= DEFT_SHAPE_LONG_SAMPLED;
+}
 inline int chunk_iters_for(int64_t elems, int32_t shape) {
-  const bool lng = shape == DEFT_SHAPE_LONG || (shape == DEFT_SHAPE_AUTO && elems > kLongVectorElems);
+  const bool lng = shape >= DEFT_SHAPE_LONG || (shape == DEFT_SHAPE_AUTO && elems > kLongVectorElems);
   return lng ? DEFT_SEL_ITERS_LARGE : DEFT_SEL_ITERS_SMALL;
+}
+// Whether a segment of a long vector is sampled ahead of its first pass: it must be long enough
+// for the sample (1/128 of it) to be cheap next to a second read, sparse enough for its
+// candidates to fit the per-chunk slots, and k/128 large enough for the sample to place the
+// threshold within two top digits.  DEFT_SHAPE_LONG_SAMPLED samples whatever can be sampled
+// (the device side still turns down what its sample cannot place).
+constexpr uint32_t kSampleMinElems = 1u << 22;
+constexpr uint32_t kSampleMinK = 12800;
+inline bool sample_segment(const SegDesc& d, int32_t shape) {
+  if (shape == DEFT_SHAPE_LONG_PLAIN || sample_pieces(d.start, d.size) == 0) return false;
+  if (shape == DEFT_SHAPE_LONG_SAMPLED) return true;
+  return d.size >= kSampleMinElems && d.k >= kSampleMinK && (uint64_t)d.k * 32u <= d.size;
 }
 
 struct SelectLayout {
-  size_t seg, st, hist, cgt, ceq, obase, ebase, tgt, teq, ccnt, hmax, slots, total;
+  size_t stats, seg, st, bnd, hist, hmax, bhist, cgt, ceq, obase, ebase, tgt, teq, ccnt, slots, total;
 };
 
 // Slots per count/emit chunk.  Measured with caps sized to the average density (4x the
@@ -1412,10 +1931,15 @@ inline uint32_t slot_cap_for(uint64_t /*total_k*/, uint64_t /*share*/, uint32_t 
 SelectLayout select_layout(int64_t m, uint64_t chunks, uint32_t cap = kMaxSlotCap) {
   SelectLayout w;
   size_t o = 0;
+  w.stats = o; o = 256;  // DEFT_STAT_ words, at the very start of the workspace
   w.seg = o;   o = align_up(o + sizeof(SegDesc) * (size_t)(m + 1), 256);
   w.st = o;    o = align_up(o + sizeof(SegState) * 4 * (size_t)m, 256);  // state after 0..3 levels
+  w.bnd = o;   o = align_up(o + sizeof(SegBound) * (size_t)m, 256);
   w.hist = o;  o = o + sizeof(uint32_t) * kHistStride * (size_t)m;  // hmax follows: zeroed together
-  w.hmax = o;  o = align_up(o + sizeof(uint32_t) * (chunks / 4 + 2 * (size_t)m + 2), 256);
+  // per-chunk maxima, then two chunk counters and the flag word of the long-vector first pass
+  w.hmax = o;  o = o + sizeof(uint32_t) * (chunks / 4 + 2 * (size_t)m + 4);
+  // the bounded histograms of the sampled segments follow directly: cleared in the same sweep
+  w.bhist = o; o = align_up(o + sizeof(uint32_t) * kBoundedStride * (size_t)std::min<int64_t>(m, kMaxSampled), 256);
   w.cgt = o;   o = align_up(o + sizeof(uint32_t) * chunks, 256);
   w.ceq = o;   o = align_up(o + sizeof(uint32_t) * chunks, 256);
   w.obase = o; o = align_up(o + sizeof(uint32_t) * chunks, 256);
@@ -1448,21 +1972,38 @@ template <int ITERS, bool FUSED>
 int launch_select(const float* g, SegDesc* seg, SegState* st, int m, uint32_t chunks,
                   uint32_t hchunks, uint32_t* hist, uint32_t* cgt, uint32_t* ceq, uint32_t* obase,
                   uint32_t* ebase, uint32_t* tgt, uint32_t* teq, uint32_t* ccnt, uint32_t* hmax,
-                  uint2* slots,
+                  uint2* slots, SegBound* bnd, uint32_t* bhist, uint32_t sblocks, uint32_t* stats,
                   uint32_t cap, bool scan_in_emit, bool dense, const SegBatch* inline_batch,
                   int32_t* idx_out, float* val_out, hipStream_t s) {
-  if (FUSED && inline_batch) {
-    hist0_inline_kernel<4 * ITERS><<<hchunks, kThreads, 0, s>>>(g, *inline_batch, seg, st, hist, hmax);
-  } else if (FUSED) {
-    hist0_kernel<4 * ITERS><<<hchunks, kThreads, 0, s>>>(g, seg, m, hist, hmax);
+  if constexpr (FUSED) {
+    if (inline_batch)
+      hist0_inline_kernel<4 * ITERS><<<hchunks, kThreads, 0, s>>>(g, *inline_batch, seg, st, hist, hmax);
+    else
+      hist0_kernel<4 * ITERS><<<hchunks, kThreads, 0, s>>>(g, seg, m, hist, hmax);
   } else {
-    // hmax[hchunks] is the chunk counter (zeroed with the histograms by seg_setup_kernel)
-    hist0_stream_kernel<4 * ITERS><<<std::min<uint32_t>(hchunks, kStreamGrid), kThreads, 0, s>>>(
-        g, seg, m, hchunks, hist, hmax, hmax + hchunks);
-    find_kernel<0><<<m, kThreads, 0, s>>>(st, m, hist);
+    // hmax[hchunks]: the chunk counter of the full first pass; hmax[hchunks + 2]: the flag word
+    // (both zeroed with the histograms by seg_setup_kernel)
+    uint32_t* flags = hmax + hchunks + 2;
+    const unsigned grid1 = std::min<uint32_t>(hchunks, kStreamGrid);
+    if (sblocks) {
+      // sampled segments: placed by the sample, read once, checked; the four launches after
+      // these are no-ops unless a segment was not sampled, turned down or refuted
+      sample_hist_kernel<<<sblocks, kThreads, 0, s>>>(g, seg, m, hist);
+      bounds_kernel<<<m, kThreads, 0, s>>>(seg, hist, bnd, flags);
+      if (cap != kStageCap) return DEFT_EINVAL;  // the staging arrays mirror the slots of this shape
+      pass1_bounded_kernel<4 * ITERS><<<hchunks, kThreads, 0, s>>>(g, seg, m, bhist, bnd, ccnt, slots, cap);
+      find_first_kernel<<<m, kThreads, 0, s>>>(st, m, seg, bhist, bnd, flags, stats);
+    } else {
+      bnd = nullptr;  // nothing sampled: every segment takes the full path, no checks needed
+    }
+    hist0_stream_kernel<4 * ITERS><<<grid1, kThreads, 0, s>>>(g, seg, m, hchunks, hist, hmax, hmax + hchunks,
+                                                              bnd, flags);
+    find_kernel<0><<<m, kThreads, 0, s>>>(st, m, hist, bnd);
   }
-  pass2_kernel<ITERS, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, st, m, hist, hmax, ccnt, slots, cap);
-  if (!FUSED) find_kernel<1><<<m, kThreads, 0, s>>>(st, m, hist);
+  pass2_kernel<ITERS, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, st, m, hist, hmax, ccnt, slots, cap,
+                                                         FUSED ? nullptr : bnd,
+                                                         FUSED ? nullptr : hmax + hchunks + 2);
+  if (!FUSED) find_kernel<1><<<m, kThreads, 0, s>>>(st, m, hist, bnd);
   if (FUSED) {
     slot_hist2_kernel<ITERS, true><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist, ccnt, slots, cap);
     slot_count_kernel<ITERS, true><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist, ccnt, slots, cap,
@@ -1471,7 +2012,7 @@ int launch_select(const float* g, SegDesc* seg, SegState* st, int m, uint32_t ch
     const uint32_t wblocks = (chunks + kWaves - 1) / kWaves;
     slot_hist2_wave_kernel<ITERS><<<std::min<uint32_t>(wblocks, kSlotWaveGrid), kThreads, 0, s>>>(
         g, seg, st, m, chunks, hist, ccnt, slots, cap);
-    find_kernel<2><<<m, kThreads, 0, s>>>(st, m, hist);
+    find_kernel<2><<<m, kThreads, 0, s>>>(st, m, hist, bnd);
     slot_count_wave_kernel<ITERS><<<wblocks, kThreads, 0, s>>>(g, seg, st, m, chunks, ccnt, slots,
                                                               cap, cgt, ceq);
   }
@@ -1500,7 +2041,8 @@ struct Precleared {
 };
 
 // Words to clear for a layout: the histograms, the per-chunk maxima and the chunk counter.
-inline size_t clear_words(const SelectLayout& w) { return (w.cgt - w.hist) / sizeof(uint32_t); }
+// (The bounded histograms behind them belong to the long-vector shape, which clears its own.)
+inline size_t clear_words(const SelectLayout& w) { return (w.bhist - w.hist) / sizeof(uint32_t); }
 
 // Enqueue the selection of `m` validated, non-empty segments (k >= 1 each).  With `pre`, short
 // selections of at most kSegBatch segments skip the set-up launch: the descriptors travel with
@@ -1515,11 +2057,18 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   const uint32_t ce = (uint32_t)kThreads * 4 * iters;
   const uint32_t hce = 4 * ce;
   std::vector<SegDesc> segs(segs_in);
-  uint64_t chunks = 0, hchunks = 0;
+  uint64_t chunks = 0, hchunks = 0, sblocks = 0;
+  uint32_t n_sampled = 0;
   uint32_t longest = 0;  // chunks of the longest segment
   for (auto& d : segs) {
     d.chunk_base = (uint32_t)chunks;
     d.hchunk_base = (uint32_t)hchunks;
+    d.sblock_base = (uint32_t)sblocks;
+    d.sampled = 0;
+    if (!small && n_sampled < kMaxSampled && sample_segment(d, shape)) {
+      d.sampled = ++n_sampled;
+      sblocks += (sample_pieces(d.start, d.size) + kSamplePiecesPerWg - 1) / kSamplePiecesPerWg;
+    }
     const uint32_t c = chunks_of(d.start, d.size, ce);
     longest = std::max(longest, c);
     chunks += c;
@@ -1539,25 +2088,30 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   char* base = static_cast<char*>(ws);
   SegDesc* seg = reinterpret_cast<SegDesc*>(base + w.seg);
   SegState* st = reinterpret_cast<SegState*>(base + w.st);
+  SegBound* bnd = reinterpret_cast<SegBound*>(base + w.bnd);
   uint32_t* hist = reinterpret_cast<uint32_t*>(base + w.hist);
   SegBatch b;
   b.total_chunks = (uint32_t)chunks;
   b.total_hchunks = (uint32_t)hchunks;
   b.m = m;
-  b.pad = 0;
+  b.total_sblocks = (uint32_t)sblocks;
   if (inline_segs) {
     b.first = 0;
     b.count = m;
     std::memcpy(b.d, segs.data(), sizeof(SegDesc) * (size_t)m);
   } else {
-    // histograms, the per-chunk maxima and the chunk counter of the long-vector first pass
-    const size_t nzero = (size_t)kHistStride * m + hchunks + 1;
+    // histograms, the per-chunk maxima, and the two chunk counters and the flag word of the
+    // long-vector first pass
+    // (long vectors: also the bounded histograms of the sampled segments, which follow)
+    const size_t nzero = small ? (size_t)kHistStride * m + hchunks + 3
+                               : (w.bhist - w.hist) / sizeof(uint32_t) + (size_t)kBoundedStride * n_sampled;
     const unsigned setup_blocks = (unsigned)std::min<size_t>((nzero + 4 * kThreads - 1) / (4 * kThreads), 256);
     for (int first = 0; first < m; first += kSegBatch) {
       b.first = first;
       b.count = std::min(kSegBatch, m - first);
       std::memcpy(b.d, segs.data() + first, sizeof(SegDesc) * (size_t)b.count);
-      seg_setup_kernel<<<first == 0 ? setup_blocks : 1, kThreads, 0, s>>>(b, seg, st, hist, nzero);
+      seg_setup_kernel<<<first == 0 ? setup_blocks : 1, kThreads, 0, s>>>(
+          b, seg, st, small ? nullptr : bnd, reinterpret_cast<uint32_t*>(base + w.stats), hist, nzero);
     }
   }
   uint32_t* cgt = reinterpret_cast<uint32_t*>(base + w.cgt);
@@ -1571,11 +2125,12 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   uint2* sl = reinterpret_cast<uint2*>(base + w.slots);
   if (small)
     return launch_select<DEFT_SEL_ITERS_SMALL, true>(
-        g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, tg, te, cc, hm, sl, cap,
-        scan_in_emit, dense, inline_segs ? &b : nullptr, idx_out, val_out, s);
+        g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, tg, te, cc, hm, sl, nullptr,
+        nullptr, 0, nullptr, cap, scan_in_emit, dense, inline_segs ? &b : nullptr, idx_out, val_out, s);
   return launch_select<DEFT_SEL_ITERS_LARGE, false>(
-      g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, tg, te, cc, hm, sl, cap,
-      scan_in_emit, dense, nullptr, idx_out, val_out, s);
+      g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, tg, te, cc, hm, sl, bnd,
+      reinterpret_cast<uint32_t*>(base + w.bhist), (uint32_t)sblocks,
+      reinterpret_cast<uint32_t*>(base + w.stats), cap, scan_in_emit, dense, nullptr, idx_out, val_out, s);
 }
 
 }  // namespace

@@ -329,11 +329,13 @@ def test_select_repeatable_and_workspace_reuse(deft):
     assert ai.tolist() == b.idx.tolist() and (_bits(av) == _bits(b.val)).all()
 
 
-@pytest.fixture
-def long_vector_shape():
-    """Force the long-vector launch shape on small inputs (it changes speed only)."""
+@pytest.fixture(params=["plain", "sampled"])
+def long_vector_shape(request):
+    """Force the long-vector launch shape on small inputs (it changes speed only), without and
+    with the sampling ahead of the first pass."""
     from paper_2307_03500_amd import binding, pipeline
-    pipeline.DEFAULT_SHAPE = binding.SHAPE_LONG
+    pipeline.DEFAULT_SHAPE = (binding.SHAPE_LONG_PLAIN if request.param == "plain"
+                              else binding.SHAPE_LONG_SAMPLED)
     yield
     pipeline.DEFAULT_SHAPE = binding.SHAPE_AUTO
 
@@ -370,6 +372,149 @@ def test_select_long_vector_shape_configs(deft, long_vector_shape):
     test_select_many_small_segments(deft)
     test_deft_path_configs_all_ranks(deft, "lstm_lm")
     test_topk_global_configs(deft, "lstm_lm")
+
+
+# ------------------------------------------------------------------------------ sampled first pass
+def _first_pass_stats(sel):
+    """[segments read once thanks to a sample, segments redone after the exact check refuted
+    the sample, segments treated in full] of the selector's last long-vector call (the
+    DEFT_STAT_ words at the start of the workspace)."""
+    torch.cuda.synchronize()
+    return sel.ws[:16].cpu().numpy().view(np.uint32)[:3].tolist()
+
+
+def _sample_positions(start, size):
+    """Element positions the long-vector kernels sample in a segment [start, start + size): 32
+    consecutive elements out of every 4096, at an offset that depends on the block number
+    (restated here from the kernel's description to build inputs that mislead the sample)."""
+    a = (start + 3) & ~3
+    pieces = max(0, (start + size - a) // 4096)
+    q = np.arange(pieces, dtype=np.uint64)
+    off = ((q * np.uint64(2654435761)) & np.uint64(0xFFFFFFFF)) >> np.uint64(25)
+    first = np.uint64(a) + q * np.uint64(4096) + off * np.uint64(32)
+    return (first[:, None] + np.arange(32, dtype=np.uint64)[None, :]).ravel().astype(np.int64)
+
+
+def _sampled_selector(sizes, out_cap=None):
+    from paper_2307_03500_amd import binding
+    return pipeline.DeftSelector(sizes, 1, 0.5, DEV, out_cap=out_cap, shape=binding.SHAPE_LONG_SAMPLED)
+
+
+@pytest.mark.parametrize("kind", ["student_t", "bf16_ties", "normal", "zero_rows", "laplace_scaled"])
+def test_sampled_first_pass_one_segment(deft, kind):
+    """Conventional Top-k with the threshold placed by a sample (one read of the vector): several
+    value distributions at a size the sorting oracle handles, K = N/100 and N/400.  (With 1/128
+    of 16 M elements sampled, K = N/100 leaves the sample's doubt within four top digits for
+    power-law tails; at K = N/400 it may not, and the segment is then treated in full.)"""
+    N = 16_000_037
+    rng = np.random.default_rng(31)
+    if kind == "student_t":
+        g = rng.standard_t(3, N) * 1e-2
+    elif kind == "bf16_ties":
+        g = rng.standard_t(3, N).astype(np.float32)
+        g = ((g.view(np.uint32) + np.uint32(0x8000)) & np.uint32(0xFFFF0000)).view(np.float32)
+    elif kind == "normal":
+        g = rng.standard_normal(N)
+    elif kind == "zero_rows":
+        g = rng.laplace(0, 1e-2, N)
+        g.reshape(-1)[: (N // 1000) * 1000].reshape(-1, 1000)[rng.random(N // 1000) < 0.7] = 0.0
+    else:  # per-block scales over four decades: a few regions hold nearly all large keys
+        g = rng.laplace(0, 1.0, N) * np.repeat(10 ** rng.uniform(-4, 0, N // 50_000 + 1), 50_000)[:N]
+    g = g.astype(np.float32)
+    sel = _sampled_selector([N])
+    gd = torch.from_numpy(g).to(DEV)
+    for K in (N // 100, N // 400):
+        gi, gv = sel.topk_global(gd, K)
+        stats = _first_pass_stats(sel)
+        oi, ov = O.topk_global(g, K)
+        assert gi.tolist() == oi.tolist() and (_bits(gv) == _bits(ov)).all()
+        assert sum(stats) == 1 and stats[1] == 0, stats   # nothing here should mislead a sample
+        if K == N // 100 and kind in ("student_t", "normal", "bf16_ties"):
+            assert stats == [1, 0, 0], stats              # and these must take the one-read path
+
+
+def test_sampled_first_pass_many_segments(deft):
+    """Layer-wise selection in the sampled long-vector shape: long and short, aligned and
+    unaligned segments with sparse, tiny and dense k side by side."""
+    sizes = [13_000_000, 40_003, 3_000_001, 5_000, 300_000, 17, 900_000]
+    k = [130_000, 400, 30_000, 50, 9_000, 17, 300_000]
+    rng = np.random.default_rng(32)
+    N = sum(sizes)
+    g = (rng.standard_t(3, N) * np.repeat(10 ** rng.uniform(-3, 0, len(sizes)), sizes)).astype(np.float32)
+    lo = sizes[0] + sizes[1]
+    g[lo:lo + sizes[2]] = (rng.standard_normal(sizes[2]) * 0.02).astype(np.float32)
+    sel = _sampled_selector(sizes, out_cap=N)
+    gd = torch.from_numpy(g).to(DEV)
+    off = sel.offsets.tolist()
+    for part in ([0, 1, 2, 3, 4, 5, 6], [6, 2, 0], [4]):
+        seg, idx_dev, val_dev = sel.select_with_plan(gd, np.asarray(k, np.int64), np.asarray(part, np.int32))
+        stats = _first_pass_stats(sel)
+        o_idx, o_val, o_seg = O.select(g, off, k, part)
+        assert seg.tolist() == o_seg.tolist()
+        assert idx_dev.cpu().numpy().tolist() == o_idx.tolist()
+        assert (_bits(val_dev.cpu().numpy()) == _bits(o_val)).all()
+        assert sum(stats) == len(part) and stats[1] == 0, stats
+        if part[0] == 0:
+            assert stats[0] == 2, stats   # the 13 M and the 3 M segment are read once
+
+
+@pytest.mark.parametrize("case", ["large_keys_hide_from_the_sample", "sample_sees_only_large_keys",
+                                  "gaps_between_digits"])
+def test_sampled_first_pass_misled_sample_is_redone(deft, case):
+    """Inputs built against the sampling positions so that the sample misplaces the threshold:
+    the exact check after the first pass must notice and the segment be redone in full, with
+    the same bits as the oracle.  (The third case is turned down before the pass: the sample
+    cannot place the threshold within two digits.)"""
+    N = 2_000_000
+    rng = np.random.default_rng(33)
+    pos = _sample_positions(0, N)
+    seen = np.zeros(N, bool)
+    seen[pos] = True
+    if case == "large_keys_hide_from_the_sample":
+        # base values uniform in (-1e-3, 1e-3): their top digit [2^-10, 1e-3] holds 2.3 % of them,
+        # more than K, so the sample confidently places the threshold there
+        g = rng.uniform(-1e-3, 1e-3, N).astype(np.float32)
+        hidden = rng.choice(np.nonzero(~seen)[0], 30_000, replace=False)
+        g[hidden] = rng.uniform(1.0, 2.0, hidden.size).astype(np.float32)
+        K, want = 20_000, [0, 1, 0]
+    elif case == "sample_sees_only_large_keys":
+        g = (rng.standard_normal(N) * 1e-3).astype(np.float32)
+        g[pos] = (2.0 ** rng.uniform(0, 20, pos.size)).astype(np.float32)
+        K, want = 10_000, [0, 1, 0]
+    else:
+        g = rng.choice(np.array([1.0, 3.0e3, 7.0e6], np.float32), N, p=[0.97, 0.02, 0.01])
+        K, want = 45_000, [0, 0, 1]
+    sel = _sampled_selector([N])
+    gd = torch.from_numpy(g).to(DEV)
+    gi, gv = sel.topk_global(gd, K)
+    stats = _first_pass_stats(sel)
+    oi, ov = O.topk_global(g, K)
+    assert gi.tolist() == oi.tolist() and (_bits(gv) == _bits(ov)).all()
+    assert stats == want, stats
+
+
+def test_sampled_first_pass_mixed_outcomes_in_one_call(deft):
+    """One call whose segments end three ways: read once, refuted and redone, in full."""
+    sizes = [2_000_000, 2_000_001, 30_000]
+    rng = np.random.default_rng(34)
+    N = sum(sizes)
+    g = rng.uniform(-1e-3, 1e-3, N).astype(np.float32)
+    s1 = sizes[0]
+    seen = np.zeros(sizes[1], bool)
+    seen[_sample_positions(s1, sizes[1]) - s1] = True
+    hidden = s1 + rng.choice(np.nonzero(~seen)[0], 30_000, replace=False)
+    g[hidden] = rng.uniform(1.0, 2.0, hidden.size).astype(np.float32)
+    k = [20_000, 20_000, 300]
+    sel = _sampled_selector(sizes, out_cap=N)
+    gd = torch.from_numpy(g).to(DEV)
+    off = sel.offsets.tolist()
+    seg, idx_dev, val_dev = sel.select_with_plan(gd, np.asarray(k, np.int64), np.asarray([2, 1, 0], np.int32))
+    stats = _first_pass_stats(sel)
+    o_idx, o_val, o_seg = O.select(g, off, k, [2, 1, 0])
+    assert seg.tolist() == o_seg.tolist()
+    assert idx_dev.cpu().numpy().tolist() == o_idx.tolist()
+    assert (_bits(val_dev.cpu().numpy()) == _bits(o_val)).all()
+    assert stats == [1, 1, 1], stats
 
 
 # ------------------------------------------------------------------------------ Alg. 1 neighbours

@@ -41,7 +41,7 @@ def _values(rng, N, kind):
 def test_random_layers_and_k(deft, seed):
     rng = np.random.default_rng(7000 + seed)
     long_shape = seed % 3 == 2
-    shape = B.SHAPE_LONG if long_shape else B.SHAPE_AUTO
+    shape = (B.SHAPE_LONG_SAMPLED if seed % 2 else B.SHAPE_LONG_PLAIN) if long_shape else B.SHAPE_AUTO
     try:
         n_layers = int(rng.integers(1, 40))
         top = int(10 ** rng.uniform(1, 5.6))
@@ -89,7 +89,7 @@ def test_random_whole_call(deft, seed):
     """deft_sparsify on random layer lists (fewer and more segments than one descriptor batch
     holds, both launch shapes) against the oracle's whole path fed the GPU's norms."""
     rng = np.random.default_rng(9000 + seed)
-    shape = B.SHAPE_LONG if seed % 4 == 3 else B.SHAPE_AUTO
+    shape = (B.SHAPE_LONG_SAMPLED if seed % 8 == 3 else B.SHAPE_LONG_PLAIN) if seed % 4 == 3 else B.SHAPE_AUTO
     try:
         n_tensors = int(rng.integers(1, 60)) if seed % 2 else int(rng.integers(150, 260))
         top = int(10 ** rng.uniform(1, 4.8))

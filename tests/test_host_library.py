@@ -183,7 +183,7 @@ def test_device_calls_reject_bad_arguments_before_touching_the_gpu(deft):
                                C.c_void_p(val), seg.ctypes.data_as(i64p), cap, C.c_void_p(ws), wsb,
                                shape, None)
 
-    assert sel(shape=3) == B.DEFT_EINVAL and sel(shape=-1) == B.DEFT_EINVAL
+    assert sel(shape=5) == B.DEFT_EINVAL and sel(shape=-1) == B.DEFT_EINVAL
     assert sel(g=0) == B.DEFT_EINVAL
     assert sel(g=0x1004) == B.DEFT_EINVAL                      # misaligned vector
     assert sel(N=17) == B.DEFT_EINVAL                          # offsets[L] != N
