@@ -32,10 +32,21 @@ def _median(x):
     return x[len(x) // 2]
 
 
+def _affinity_cores():
+    try:
+        return len(os.sched_getaffinity(0))
+    except AttributeError:
+        return os.cpu_count() or 1
+
+
 def cpu_baseline(gs, offsets, rank, runs=3):
     """The oracle's DEFT path (fp64 norms, Alg. 3, Alg. 4, full sort per layer) on this machine's
-    host cores, as it stands; median of `runs` runs of the whole workload."""
+    host cores, as it stands: (1) on one core, the definitional number, median of `runs` runs of
+    the whole workload; (2) with the layers spread over a thread pool as wide as the affinity
+    mask (numpy's sort and its reductions release the interpreter lock), one run.  Layers are
+    independent, so (2) is the same computation."""
     import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
     from oracle import deft_oracle as O
     lay = np.diff(offsets).tolist()
     times = []
@@ -49,10 +60,30 @@ def cpu_baseline(gs, offsets, rank, runs=3):
     t = sorted(times)[len(times) // 2]
     S_r = sum(lay[p] for p in part)
     nbytes = 4 * gs.N + 4 * S_r + 8 * len(idx)
-    return {"value": nbytes / t / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"whole DEFT path of the same workload (all {gs.N} elements normed, rank "
-                      f"{rank}'s {S_r}-element share sorted), median of {runs} runs, {t:.2f} s each",
-            "seconds": t}, idx
+    one = {"value": nbytes / t / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+           "sample": f"whole DEFT path of the same workload (all {gs.N} elements normed, rank "
+                     f"{rank}'s {S_r}-element share sorted), median of {runs} runs, {t:.2f} s each",
+           "seconds": t}
+    cores = _affinity_cores()
+    L = len(lay)
+    with ThreadPoolExecutor(max_workers=cores) as pool:
+        t0 = time.perf_counter()
+        # norms: contiguous groups of layers, one group per worker
+        step = max(1, -(-L // cores))
+        groups = [list(range(a, min(L, a + step))) for a in range(0, L, step)]
+        parts = list(pool.map(lambda ls: O.layer_norms(gs.g, [offsets[ls[0]]] + [offsets[l + 1] for l in ls]),
+                              groups))
+        norms_p = np.concatenate(parts)
+        k_p = O.alloc_k(norms_p, lay, gs.N, gs.d)
+        _, part_p, _ = O.assign_layers(lay, k_p, gs.n_workers, 0, rank)
+        picks = list(pool.map(lambda l: O.select(gs.g, offsets, k_p, [l])[0], part_p))
+        tp = time.perf_counter() - t0
+    idx_p = np.concatenate(picks) if picks else np.zeros(0, np.int64)
+    par = {"value": nbytes / tp / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+           "sample": "the same workload, layers spread over a thread pool as wide as the affinity "
+                     f"mask ({cores} threads), one run, {tp:.2f} s",
+           "seconds": tp, "same_result": bool(len(idx_p) == len(idx) and (idx_p == idx).all())}
+    return one, par, idx
 
 
 def sweep_workers(args, ns):
@@ -249,10 +280,18 @@ def main():
         # no sync here: the next step's norm pass queues behind this step's selection (same
         # stream, same buffers); the host only waits where the method needs it, for the norms
         # (inside the call).  The K steps are bracketed by synchronisations on both sides.
+    end_ev = torch.cuda.Event(enable_timing=True)
+    end_ev.record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     norm_ms = [e[0].elapsed_time(e[1]) for i, e in enumerate(ev) if i % args.event_every == 0]
+    # per-step times on the device clock: from the event at the head of one step to the next
+    # one's (the last step to the event behind it); median and minimum next to the mean above
+    step_ms = []
+    if args.event_every == 1:
+        heads = [e[0] for e in ev] + [end_ev]
+        step_ms = [heads[i].elapsed_time(heads[i + 1]) for i in range(args.steps)]
 
     # host plan alone (Alg. 3 + Alg. 4 on the sums just delivered), outside the timed region
     plan_ms = []
@@ -283,13 +322,30 @@ def main():
         B.topk_global(g, K, sel.idx_out, sel.val_out, sel.ws)
     torch.cuda.synchronize()
     gsteps = max(5, args.steps // 2)
+    gev = [torch.cuda.Event(enable_timing=True) for _ in range(gsteps + 1)]
     g0 = time.perf_counter()
-    for _ in range(gsteps):
+    for i in range(gsteps):
+        gev[i].record(stream)
         B.topk_global(g, K, sel.idx_out, sel.val_out, sel.ws)
+    gev[gsteps].record(stream)
     stream.synchronize()
     g1 = time.perf_counter()
     global_ms = (g1 - g0) * 1e3 / gsteps
+    global_each = [gev[i].elapsed_time(gev[i + 1]) for i in range(gsteps)]
     global_gbps = (4 * N + 8 * K) / (global_ms * 1e-3) / 1e9
+
+    # ---- the read rate the norm pass's access pattern reaches on this machine (load-only probe)
+    probe_out = torch.zeros(4, dtype=torch.int32, device=dev)
+    pev = [torch.cuda.Event(enable_timing=True) for _ in range(11)]
+    for _ in range(3):
+        B.deft_stream_read_probe(g, probe_out)
+    for i in range(10):
+        pev[i].record(stream)
+        B.deft_stream_read_probe(g, probe_out)
+    pev[10].record(stream)
+    stream.synchronize()
+    probe_ms = sorted(pev[i].elapsed_time(pev[i + 1]) for i in range(10))
+    ceiling = 4.0 * (N - N % 4096) / (probe_ms[len(probe_ms) // 2] * 1e-3) / 1e9
 
     # ---- Alg. 5 alone on every rank (the slowest worker sets the time, Eq. 5)
     per_rank = None
@@ -347,16 +403,22 @@ def main():
     norm_avg_ms = sum(norm_ms) / len(norm_ms)
     achieved = 4.0 * N / (norm_avg_ms * 1e-3) / 1e9
     traffic = None
+    traffic_all = {}
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(args.config, {}).get("norm_chunks_kernel")
+            traffic_all = json.load(open(tpath)).get(args.config, {})
+            traffic = traffic_all.get("norm_chunks_kernel")
         except Exception:
             traffic = None
+    cache_bytes = 256 * 2 ** 20  # MI355X Infinity Cache
     roofline = {"kernel": "norm_chunks_kernel (+ norm_finish_kernel inside the same event pair)",
                 "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                "bytes_per_launch": 4 * N, "avg_launch_ms": norm_avg_ms}
+                "bytes_per_launch": 4 * N, "avg_launch_ms": norm_avg_ms,
+                "measured_stream_ceiling": ceiling, "frac_of_ceiling": achieved / ceiling,
+                "ceiling_note": "median of 10 load-only passes over the same vector in the norm "
+                                "pass's launch shape (deft_stream_read_probe), HIP events"}
 
     out = {
         "metric": "selection ms/iter & GB/s scanned (norms+top-k) vs HBM peak, per worker share",
@@ -371,6 +433,9 @@ def main():
                    "share_layers": int(len(mine)), "S_r": S_r, "k_r": k_r,
                    "sum_k_minus_K": int(k.sum()) - K},
         "frac_of_hbm_peak": value / HBM_PEAK_GBPS,
+        "ms_per_step_device": ({"median": _median(step_ms), "min": min(step_ms)} if step_ms else None),
+        "fits_infinity_cache": {"vector_4N": 4 * N <= cache_bytes, "share_4S_r": 4 * S_r <= cache_bytes,
+                                "cache_bytes": cache_bytes},
         "entry": "step-wise calls" if args.stepwise else "deft_sparsify",
         # norm_pass: event pairs inside the timed steps.  host_plan and select are timed apart
         # from them (the three host calls through the binding; deft_select alone, which includes
@@ -381,10 +446,19 @@ def main():
                      "select": _median(select_ms),
                      "remainder": ms_per_step - _median(norm_ms) - _median(plan_ms)
                      - _median(select_ms)},
-        "select_only": {"ms": _median(select_ms),
-                        "GB/s": (4 * S_r + 8 * k_r) / (_median(select_ms) * 1e-3) / 1e9},
-        "topk_global": {"ms": global_ms, "GB/s": global_gbps, "frac_of_hbm_peak": global_gbps / HBM_PEAK_GBPS,
-                        "steps": gsteps},
+        "select_only": {"ms": _median(select_ms), "ms_min": min(select_ms),
+                        "GB/s": (4 * S_r + 8 * k_r) / (_median(select_ms) * 1e-3) / 1e9,
+                        "algorithmic_bytes": 4 * S_r + 8 * k_r,
+                        "traffic": traffic_all.get("deft_select"),
+                        "traffic_ratio": (traffic_all["deft_select"] / (4 * S_r + 8 * k_r)
+                                          if traffic_all.get("deft_select") else None)},
+        "topk_global": {"ms": global_ms, "ms_median": _median(global_each), "ms_min": min(global_each),
+                        "GB/s": global_gbps, "frac_of_hbm_peak": global_gbps / HBM_PEAK_GBPS,
+                        "frac_of_ceiling": global_gbps / ceiling, "steps": gsteps,
+                        "algorithmic_bytes": 4 * N + 8 * K,
+                        "traffic": traffic_all.get("topk_global"),
+                        "traffic_ratio": (traffic_all["topk_global"] / (4 * N + 8 * K)
+                                          if traffic_all.get("topk_global") else None)},
         "speedup_vs_topk_global": {"select_only": global_ms / _median(select_ms),
                                    "whole_path": global_ms / ms_per_step,
                                    "f_n_cost_model": cm["f_n"], "f_trivial": cm["f_trivial"]},
@@ -395,8 +469,9 @@ def main():
     if next_rows is not None:
         out["next_rows"] = next_rows
     if not args.no_cpu_baseline:
-        cb, o_idx = cpu_baseline(gs, sel.offsets.tolist(), rank)
+        cb, cb_par, o_idx = cpu_baseline(gs, sel.offsets.tolist(), rank)
         out["cpu_baseline"] = cb
+        out["cpu_baseline_all_cores"] = cb_par
         out["oracle_match"] = bool(len(first_idx) == len(o_idx) and (first_idx == o_idx).all())
     print(json.dumps(out))
 

@@ -267,6 +267,16 @@ int deft_gather_zero(float* acc_dev, int64_t N, const int32_t* idx_dev, int64_t 
                      float* vals_out_dev, void* stream);
 
 /*
+ * Measurement aid, not a step of the method: one streaming read of the first N - N mod 4096
+ * elements of g in the launch shape of deft_layer_norms and nothing else.  Its duration gives the
+ * read rate this access pattern reaches on the machine at hand, the ceiling the passes of
+ * deft_layer_norms and of the selection are measured against.
+ *   out_dev  out  at least 4 bytes of device memory (hardly ever written)
+ * Errors: DEFT_EINVAL (null, N < 4096, misaligned g), DEFT_ERANGE, DEFT_EHIP.
+ */
+int deft_stream_read_probe(const float* g_dev, int64_t N, void* out_dev, void* stream);
+
+/*
  * One sparsifier call (Sec. 4, opening paragraph: norms -> local k -> layer allocation ->
  * layer-wise selection; the Sparsify() of Alg. 1) as a single entry point: the same work, in
  * the same order and with the same results, as

@@ -37,6 +37,7 @@ SIGNATURES = {
     "deft_accumulate_norms": (C.c_int, [_P, _P, C.c_float, _P, C.c_int64, _P, C.c_int32, _P, _P,
                                         C.c_size_t, _P]),
     "deft_gather_zero": (C.c_int, [_P, C.c_int64, _P, C.c_int64, _P, _P]),
+    "deft_stream_read_probe": (C.c_int, [_P, C.c_int64, _P, _P]),
     "deft_alloc_k": (C.c_int, [_P, _P, C.c_int32, C.c_int64, C.c_double, _P]),
     "deft_assign_layers": (C.c_int, [_P, _P, C.c_int32, C.c_int32, C.c_int64, C.c_int32, _P, _P, _P]),
     "deft_cost_model": (C.c_int, [_P, _P, _P, C.c_int32, C.c_int32, C.c_int64, C.c_int64, _P, _P]),
@@ -214,6 +215,12 @@ def deft_gather_zero(acc, idx, vals_out, stream=None) -> None:
     """vals_out[i] = acc[idx[i]]; acc[idx[i]] = 0.  idx: int32 cuda tensor of distinct positions."""
     _check(lib().deft_gather_zero(acc.data_ptr(), acc.numel(), idx.data_ptr(), idx.numel(),
                                   vals_out.data_ptr(), _stream(stream)), "deft_gather_zero")
+
+
+def deft_stream_read_probe(g, out, stream=None) -> None:
+    """Measurement aid: one streaming read of g in the norm pass's launch shape."""
+    _check(lib().deft_stream_read_probe(g.data_ptr(), g.numel(), out.data_ptr(), _stream(stream)),
+           "deft_stream_read_probe")
 
 
 def deft_select(g, offsets_host, k_host, my_layers_host, idx_out, val_out, ws, stream=None,

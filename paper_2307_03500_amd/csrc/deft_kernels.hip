@@ -196,6 +196,23 @@ __global__ __launch_bounds__(kThreads) void norm_chunks_kernel(
   norm_one_chunk<ACC>(src, N, off, L, head, tail, sumsq, blockIdx.x, red);
 }
 
+// Measurement aid: reads the vector once in the launch shape of the norm pass (fixed chunks of
+// kNormChunk elements, kNormIters streaming 16-byte loads per thread) and does nothing else but
+// fold the words together; the time of this kernel is the read rate the access pattern can reach
+// on the machine at hand.  The fold is stored only if it hits one particular value, which keeps
+// the loads alive without a store per workgroup.
+__global__ __launch_bounds__(kThreads) void stream_probe_kernel(const float* __restrict__ g,
+                                                                uint32_t* __restrict__ out) {
+  const v4u* __restrict__ p = reinterpret_cast<const v4u*>(g + (int64_t)blockIdx.x * kNormChunk);
+  v4u v[kNormIters];
+#pragma unroll
+  for (int i = 0; i < kNormIters; ++i) v[i] = __builtin_nontemporal_load(&p[threadIdx.x + i * kThreads]);
+  uint32_t x = 0;
+#pragma unroll
+  for (int i = 0; i < kNormIters; ++i) x ^= v[i].x ^ v[i].y ^ v[i].z ^ v[i].w;
+  if (x == 0x9E3779B9u) out[0] = x;
+}
+
 // vals[i] = acc[idx[i]]; acc[idx[i]] = 0   (Alg. 1, the steps after the index exchange)
 __global__ __launch_bounds__(kThreads) void gather_zero_kernel(float* __restrict__ acc, int64_t N,
                                                                const int32_t* __restrict__ idx,
@@ -2080,8 +2097,13 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   uint64_t total_k = 0;
   for (const auto& d : segs) total_k += d.k;
   const uint32_t cap = slot_cap_for(total_k, (uint64_t)share, ce);
-  // more than a quarter of a slot array per chunk expected on average
-  const bool dense = (double)ce * (double)total_k > 0.25 * cap * (double)share;
+  // More than a tenth of a slot array per chunk expected on average: the ordered write then
+  // takes a workgroup per chunk (measured on the BERT-shaped set, K = N/100, where a chunk holds
+  // about 80 picks: 26.7 us against 36.0 us with a wavefront per chunk).
+#ifndef DEFT_DENSE_FRAC
+#define DEFT_DENSE_FRAC 0.1
+#endif
+  const bool dense = (double)ce * (double)total_k > DEFT_DENSE_FRAC * cap * (double)share;
   const bool inline_segs = pre && small && m <= kSegBatch && m <= pre->m_cap && chunks <= pre->chunks_cap;
   const SelectLayout w = inline_segs ? select_layout(pre->m_cap, pre->chunks_cap, cap) : select_layout(m, chunks, cap);
   if (w.total > ws_bytes) return DEFT_EWS;
@@ -2202,6 +2224,16 @@ extern "C" int deft_accumulate_norms(const float* e_dev, const float* grad_dev, 
     return DEFT_EINVAL;
   return run_norms(e_dev, grad_dev, eta, acc_dev, N, offsets_dev, L, sumsq_dev, ws_dev, ws_bytes,
                    stream);
+}
+
+extern "C" int deft_stream_read_probe(const float* g_dev, int64_t N, void* out_dev, void* stream) {
+  if (!g_dev || !out_dev || N < kNormChunk) return DEFT_EINVAL;
+  if (N > kMaxN) return DEFT_ERANGE;
+  if (reinterpret_cast<uintptr_t>(g_dev) & 15u) return DEFT_EINVAL;
+  stream_probe_kernel<<<(unsigned)(N / kNormChunk), kThreads, 0, static_cast<hipStream_t>(stream)>>>(
+      g_dev, static_cast<uint32_t*>(out_dev));
+  HIP_TRY(hipGetLastError());
+  return DEFT_OK;
 }
 
 extern "C" int deft_gather_zero(float* acc_dev, int64_t N, const int32_t* idx_dev, int64_t count,
