@@ -283,11 +283,14 @@ struct SegBound {
   uint32_t mode;
   uint32_t b_lo;
   uint32_t pad[2];
-  uint32_t hi[kHiCopies];  // keys above the four digits, counted by the first pass (copies as for the
-                           // histograms: workgroup b adds to hi[b % kHiCopies])
+  // Counted by the first pass, in copies as for the histograms (workgroup b adds to
+  // hi[b % kHiCopies]), two counts per word so that one atomic carries both: low half, the keys
+  // above the four digits; high half, the parked keys whose low kBits2 bits are not all zero.
+  unsigned long long hi[kHiCopies];
 };
 // Bits of the flag word the first bucket search leaves for the kernels behind it.
-constexpr uint32_t kFlagPass2 = 2u;  // some segment needs the full first pass and pass 2
+constexpr uint32_t kFlagPass2 = 2u;   // some segment needs the full first pass and pass 2
+constexpr uint32_t kFlagLevel2 = 4u;  // some segment's threshold still lacks its last digit
 
 struct SegState {
   uint32_t prefix;  // key bits fixed so far (right-aligned)
@@ -477,12 +480,12 @@ constexpr int kRep12 = DEFT_HIST12_COPIES;
 // Level 3 is not a fourth digit: it names the 4096-bin histogram that the first pass of a
 // sampled long-vector segment builds over the four top digits around the threshold (12 bits of
 // 2^10 keys each), which then stands for levels 0 and 1 together.  It has storage of its own, in
-// kRepB copies: with rounded gradients every workgroup that parks anything adds to the same few
-// dozen bins, and with three copies those merges cost 10 us of a 216 us pass over 1.42 GB.
+// kRepB copies (4, 8 and 16 copies: 219 / 223 / 225 us for the pass over 1.42 GB, within noise of
+// each other; the search behind it reads them all: 4.8 / 6.1 / 8.6 us).
 // A launch gives at most kMaxSampled segments such a histogram (it samples no more than that).
 constexpr int kBitsB = 12;
 #ifndef DEFT_BOUNDED_COPIES
-#define DEFT_BOUNDED_COPIES 8
+#define DEFT_BOUNDED_COPIES 4
 #endif
 constexpr int kRepB = DEFT_BOUNDED_COPIES;
 constexpr int kBoundedStride = (1 << kBitsB) * kRepB;
@@ -1028,8 +1031,12 @@ __device__ __forceinline__ uint32_t park_chunk(const float* __restrict__ g, int6
     return rel < (4u << kShift) ? (rel >> kBits2) : (uint32_t)kBinsB;
   };
   auto one = [&](uint32_t rawv, uint32_t idx, uint32_t pos) {
-    if (pos < kStageCap) stage[pos] = make_uint2(rawv, idx);
-    else atomicAdd(&lh[bin_of(rawv)], 1u);  // beyond the slots: counted, not kept
+    if (pos < kStageCap) {
+      stage[pos] = make_uint2(rawv, idx);
+    } else {  // beyond the slots: counted, not kept
+      atomicAdd(&lh[bin_of(rawv)], 1u);
+      if (rawv & ((1u << kBits2) - 1u)) atomicAdd(&lh[kBinsB + 2], 1u);
+    }
   };
   auto park = [&](const VecBatch& B, int t0) {
 #pragma unroll
@@ -1088,10 +1095,18 @@ __device__ __forceinline__ uint32_t park_chunk(const float* __restrict__ g, int6
   }
   // the staged entries (written and read by this wavefront only) leave for the slots
   const uint32_t kept = min(filled, kStageCap);
+  uint32_t low_set = 0;
   for (uint32_t r = lane; r < kept; r += 64) {
     const uint2 en = stage[r];
     my_slots[r] = en;
     atomicAdd(&lh[bin_of(en.x)], 1u);
+    low_set += (en.x & ((1u << kBits2) - 1u)) ? 1u : 0u;
+  }
+  // how many parked keys have any of their low kBits2 bits set: if none has (gradients that
+  // went through a 16-bit format), the 21 bits resolved by this pass are the whole key
+  if (__ballot(low_set != 0) != 0ull) {
+    low_set = wave_sum_u32(low_set);
+    if (lane == 0) atomicAdd(&lh[kBinsB + 2], low_set);
   }
   return filled;
 }
@@ -1106,13 +1121,14 @@ __global__ __launch_bounds__(kThreads) void pass1_bounded_kernel(
   static_assert(HITERS % kBatchVecs == 0 && (!kBatchDouble || HITERS % (2 * kBatchVecs) == 0),
                 "a wavefront's vectors split into whole batches (pairs of them when double-buffered)");
   constexpr int kElems = kThreads * 4 * HITERS;  // elements of a histogram chunk
-  // kBinsB bins over the four digits, the count of the keys above them in [kBinsB], and in
-  // [kBinsB + 1] whether this workgroup has parked anything at all
-  __shared__ uint32_t lh[kBinsB + 2];
+  // kBinsB bins over the four digits, the count of the keys above them in [kBinsB], in
+  // [kBinsB + 1] whether this workgroup has parked anything at all, in [kBinsB + 2] the number of
+  // parked keys with a low bit set
+  __shared__ uint32_t lh[kBinsB + 3];
   __shared__ uint2 stage[kWaves][kStageCap];
   const int j = seg_of_hchunk(seg, m, blockIdx.x);
   if (bnd[j].mode != kModeBounded) return;
-  for (int b = threadIdx.x; b < kBinsB + 2; b += kThreads) lh[b] = 0;
+  for (int b = threadIdx.x; b < kBinsB + 3; b += kThreads) lh[b] = 0;
   const SegDesc d = seg[j];
 #ifdef DEFT_PROBE_NOPARK  // measurement only: nothing is ever parked (the check then fails: redone in full)
   const uint32_t lo_key = (bnd[j].b_lo << kShift) | 0x7FF00000u;
@@ -1145,7 +1161,9 @@ __global__ __launch_bounds__(kThreads) void pass1_bounded_kernel(
     const uint32_t v = lh[b];
     if (v) atomicAdd(&gh[b], v);
   }
-  if (threadIdx.x == 0 && lh[kBinsB]) atomicAdd(&bnd[j].hi[blockIdx.x % kHiCopies], lh[kBinsB]);
+  if (threadIdx.x == 0 && (lh[kBinsB] | lh[kBinsB + 2]))
+    atomicAdd(&bnd[j].hi[blockIdx.x % kHiCopies],
+              (unsigned long long)lh[kBinsB] | ((unsigned long long)lh[kBinsB + 2] << 32));
 }
 
 // Pass 2 (the second, partial read).  The top digit b0 of the threshold is known.  Every key that can
@@ -1283,7 +1301,8 @@ __global__ __launch_bounds__(kThreads) void slot_hist2_kernel(
 template <int LEVEL>
 __global__ __launch_bounds__(kThreads) void find_kernel(SegState* __restrict__ st, int m,
                                                         const uint32_t* __restrict__ hist,
-                                                        const SegBound* __restrict__ bnd) {
+                                                        const SegBound* __restrict__ bnd,
+                                                        uint32_t* __restrict__ flags) {
   __shared__ uint32_t fl[kWaves + 8];
   const int j = blockIdx.x;
   // a segment whose first pass covered two digit levels already has its state after level 1
@@ -1292,7 +1311,10 @@ __global__ __launch_bounds__(kThreads) void find_kernel(SegState* __restrict__ s
   LevelBins<LEVEL> bins;
   bins.load(hist + (size_t)j * kHistStride + hist_offset(LEVEL));
   if (!s.done) s = find_bucket<LEVEL>(bins, s, fl);
-  if (threadIdx.x == 0) st[(size_t)(LEVEL + 1) * m + j] = s;
+  if (threadIdx.x == 0) {
+    st[(size_t)(LEVEL + 1) * m + j] = s;
+    if (LEVEL == 1 && flags && !s.done) atomicOr(flags, kFlagLevel2);
+  }
 }
 
 // The exact check behind the first pass over kModeBounded segments, one workgroup per segment:
@@ -1324,8 +1346,9 @@ __global__ __launch_bounds__(kThreads) void find_first_kernel(SegState* __restri
   if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = mid;
   __syncthreads();
   const uint32_t c_mid = wsum[0] + wsum[1] + wsum[2] + wsum[3];
-  uint32_t c_hi = 0;
-  for (int q = 0; q < kHiCopies; ++q) c_hi += bnd[j].hi[q];
+  unsigned long long both = 0;
+  for (int q = 0; q < kHiCopies; ++q) both += bnd[j].hi[q];
+  const uint32_t c_hi = (uint32_t)both, low_set = (uint32_t)(both >> 32);
   const uint32_t k = s.k_rem;
   if (c_hi < k && (uint64_t)k <= (uint64_t)c_hi + c_mid) {
     SegState t = s;
@@ -1338,10 +1361,18 @@ __global__ __launch_bounds__(kThreads) void find_first_kernel(SegState* __restri
     o.done = t.done;
     o.T = t.done ? (o.prefix << kBits2) : 0u;  // the whole bucket is taken
     o.r = t.done ? 0xFFFFFFFFu : 0u;
+    if (!o.done && low_set == 0u) {
+      // no parked key has any of its low bits set: the bucket holds one key value, which is the
+      // threshold, and the last digit level has nothing left to find
+      o.T = o.prefix << kBits2;
+      o.r = o.k_rem;
+      o.done = 1;
+    }
     if (threadIdx.x == 0) {
       st[(size_t)m + j] = o;
       st[(size_t)2 * m + j] = o;
       atomicAdd(&stats[DEFT_STAT_BOUNDED], 1u);
+      if (!o.done) atomicOr(flags, kFlagLevel2);
     }
   } else if (threadIdx.x == 0) {
     bnd[j].mode = kModeFailed;
@@ -1411,7 +1442,9 @@ template <int ITERS>
 __global__ __launch_bounds__(kThreads) void slot_hist2_wave_kernel(
     const float* __restrict__ g, const SegDesc* __restrict__ seg, const SegState* __restrict__ st,
     int m, uint32_t chunks, uint32_t* __restrict__ hist, const uint32_t* __restrict__ live_cnt,
-    const uint2* __restrict__ slots, uint32_t cap) {
+    const uint2* __restrict__ slots, uint32_t cap, const uint32_t* __restrict__ flags) {
+  // (a launch that sampled: nothing to do if every threshold is already resolved)
+  if (flags && !(*flags & kFlagLevel2)) return;
   // The workgroups stride over groups of kWaves consecutive chunks and collect the digits in an
   // LDS histogram that is merged into the segment's when the segment changes and at the end:
   // rounded gradients put every candidate into the same few bins, and one device-scope atomic
@@ -2015,12 +2048,12 @@ int launch_select(const float* g, SegDesc* seg, SegState* st, int m, uint32_t ch
     }
     hist0_stream_kernel<4 * ITERS><<<grid1, kThreads, 0, s>>>(g, seg, m, hchunks, hist, hmax, hmax + hchunks,
                                                               bnd, flags);
-    find_kernel<0><<<m, kThreads, 0, s>>>(st, m, hist, bnd);
+    find_kernel<0><<<m, kThreads, 0, s>>>(st, m, hist, bnd, nullptr);
   }
   pass2_kernel<ITERS, FUSED><<<hchunks, kThreads, 0, s>>>(g, seg, st, m, hist, hmax, ccnt, slots, cap,
                                                          FUSED ? nullptr : bnd,
                                                          FUSED ? nullptr : hmax + hchunks + 2);
-  if (!FUSED) find_kernel<1><<<m, kThreads, 0, s>>>(st, m, hist, bnd);
+  if (!FUSED) find_kernel<1><<<m, kThreads, 0, s>>>(st, m, hist, bnd, bnd ? hmax + hchunks + 2 : nullptr);
   if (FUSED) {
     slot_hist2_kernel<ITERS, true><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist, ccnt, slots, cap);
     slot_count_kernel<ITERS, true><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist, ccnt, slots, cap,
@@ -2028,8 +2061,8 @@ int launch_select(const float* g, SegDesc* seg, SegState* st, int m, uint32_t ch
   } else {
     const uint32_t wblocks = (chunks + kWaves - 1) / kWaves;
     slot_hist2_wave_kernel<ITERS><<<std::min<uint32_t>(wblocks, kSlotWaveGrid), kThreads, 0, s>>>(
-        g, seg, st, m, chunks, hist, ccnt, slots, cap);
-    find_kernel<2><<<m, kThreads, 0, s>>>(st, m, hist, bnd);
+        g, seg, st, m, chunks, hist, ccnt, slots, cap, bnd ? hmax + hchunks + 2 : nullptr);
+    find_kernel<2><<<m, kThreads, 0, s>>>(st, m, hist, bnd, nullptr);
     slot_count_wave_kernel<ITERS><<<wblocks, kThreads, 0, s>>>(g, seg, st, m, chunks, ccnt, slots,
                                                               cap, cgt, ceq);
   }
