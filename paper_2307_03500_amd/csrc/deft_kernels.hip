@@ -158,6 +158,29 @@ __device__ __forceinline__ void norm_one_chunk(
         a0 = fma(z, z, a0);
         a1 = fma(w, w, a1);
       }
+#ifdef DEFT_PROBE_NORM_HIST
+      // Measurement only: the top-digit histogram of every layer gathered by the norm pass itself
+      // (per-workgroup LDS histogram, merged into the layer's with one atomic per occupied bin),
+      // into scratch 64 MB behind the partial sums.  Not part of any result.
+      {
+        __shared__ uint32_t ph[2048];
+        for (int b = threadIdx.x; b < 2048; b += kThreads) ph[b] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kNormIters; ++i) {
+          atomicAdd(&ph[(__float_as_uint(v[i].x) & 0x7FFFFFFFu) >> 20], 1u);
+          atomicAdd(&ph[(__float_as_uint(v[i].y) & 0x7FFFFFFFu) >> 20], 1u);
+          atomicAdd(&ph[(__float_as_uint(v[i].z) & 0x7FFFFFFFu) >> 20], 1u);
+          atomicAdd(&ph[(__float_as_uint(v[i].w) & 0x7FFFFFFFu) >> 20], 1u);
+        }
+        __syncthreads();
+        uint32_t* gh = reinterpret_cast<uint32_t*>(head) + (16u << 20) + (size_t)lf * 2048;
+        for (int b = threadIdx.x; b < 2048; b += kThreads) {
+          const uint32_t c = ph[b];
+          if (c) atomicAdd(&gh[b], c);
+        }
+      }
+#endif
     } else {
       for (int64_t i = cs + threadIdx.x; i < ce; i += kThreads) {
         const double x = norm_value<ACC>(src, i);
@@ -1153,9 +1176,6 @@ __global__ __launch_bounds__(kThreads) void pass1_bounded_kernel(
   }
   __syncthreads();
   if (!lh[kBinsB + 1]) return;  // nothing parked (the common case in layers of small magnitude)
-#ifdef DEFT_PROBE_NOMERGE  // measurement only: the check then fails and the segment is redone in full
-  if (lo_key) return;
-#endif
   uint32_t* gh = bhist + (size_t)(d.sampled - 1) * kBoundedStride + (blockIdx.x % kRepB) * kBinsB;
   for (int b = threadIdx.x; b < kBinsB; b += kThreads) {
     const uint32_t v = lh[b];
