@@ -2127,7 +2127,7 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   const uint32_t ce = (uint32_t)kThreads * 4 * iters;
   const uint32_t hce = 4 * ce;
   std::vector<SegDesc> segs(segs_in);
-  uint64_t chunks = 0, hchunks = 0, sblocks = 0;
+  uint64_t chunks = 0, hchunks = 0, sblocks = 0, sampled_elems = 0;
   uint32_t n_sampled = 0;
   uint32_t longest = 0;  // chunks of the longest segment
   for (auto& d : segs) {
@@ -2138,11 +2138,21 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
     if (!small && n_sampled < kMaxSampled && sample_segment(d, shape)) {
       d.sampled = ++n_sampled;
       sblocks += (sample_pieces(d.start, d.size) + kSamplePiecesPerWg - 1) / kSamplePiecesPerWg;
+      sampled_elems += d.size;
     }
     const uint32_t c = chunks_of(d.start, d.size, ce);
     longest = std::max(longest, c);
     chunks += c;
     hchunks += chunks_of(d.start, d.size, hce);
+  }
+  // Sampling adds four launches and a sweep of early-leaving workgroups over every chunk; it pays
+  // when most of what is selected from is then read once.  (Layer-wise selection of one worker
+  // of 4 on the GPT-2-medium-shaped set, where only a few of 80 segments qualify: 245 us without
+  // any sampling, 270 us with.)
+  if (shape != DEFT_SHAPE_LONG_SAMPLED && 2 * sampled_elems < (uint64_t)share) {
+    for (auto& d : segs) d.sampled = 0;
+    n_sampled = 0;
+    sblocks = 0;
   }
   // every emit workgroup can afford to sum its segment's earlier chunk counts itself
   const bool scan_in_emit = longest <= 2048;
