@@ -1882,7 +1882,12 @@ __global__ __launch_bounds__(kThreads) void emit_wave_kernel(
   bool over = false;
   uint32_t eb = 0, ob = 0;
   if (c < chunks) {
+    // everything that is indexed by the chunk alone is fetched at once, ahead of the chain
+    // segment -> state -> prefixes -> slots (each link a round trip to memory)
     const uint32_t cgt = chunk_gt[c], ceq = chunk_eq[c];
+    const uint32_t pg = pre_gt[c], pe = pre_eq[c], n = live_cnt[c];
+    const uint2 first = (n != 0 && n <= cap && (uint32_t)lane < n) ? slots[(size_t)c * cap + lane]
+                                                                 : make_uint2(0u, 0u);
     if (cgt != 0 || ceq != 0) {
       const int j = seg_of_chunk(seg, m, c);
       const SegDesc d = seg[j];
@@ -1897,11 +1902,10 @@ __global__ __launch_bounds__(kThreads) void emit_wave_kernel(
       }
       sg = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_sum_u32(sg));
       se = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_sum_u32(se));
-      const uint32_t gt_before = sg + pre_gt[c] - pre_gt[c0];
-      eb = se + pre_eq[c] - pre_eq[c0];
+      const uint32_t gt_before = sg + pg - pre_gt[c0];
+      eb = se + pe - pre_eq[c0];
       ob = d.out_off + gt_before + min(r, eb);
       if (!(cgt == 0 && eb >= r)) {
-        const uint32_t n = live_cnt[c];
         if (n > cap) {
           over = true;
         } else {
@@ -1911,7 +1915,7 @@ __global__ __launch_bounds__(kThreads) void emit_wave_kernel(
           uint32_t pos = ob, rank = eb;
           for (uint32_t r0 = 0; r0 < n; r0 += 64) {
             const bool on = r0 + lane < n;
-            const uint2 e = on ? slots[(size_t)c * cap + r0 + lane] : make_uint2(0u, 0u);
+            const uint2 e = r0 == 0 ? first : (on ? slots[(size_t)c * cap + r0 + lane] : make_uint2(0u, 0u));
             const uint32_t key = e.x & 0x7FFFFFFFu;
             const bool is_eq = on && key == T;
             bool take = on && key > T;
