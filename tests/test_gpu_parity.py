@@ -793,6 +793,31 @@ def test_maximum_vector_length(deft):
     torch.cuda.empty_cache()
 
 
+def test_maximum_vector_length_sampled_one_read_path(deft):
+    """N = 2^31 - 5 through the sampled one-read path of the conventional Top-k: zeros everywhere
+    except the last 64 M elements (normal values), so that the answer is the Top-k of that region
+    and the sorting oracle can produce it, while the kernels run over every chunk of the vector
+    with indices up to 2^31 - 6.  K = 1 % of the region: the sample places the threshold and the
+    segment is read once (asserted through the diagnostics words)."""
+    N = 2 ** 31 - 5
+    R = 64 * 2 ** 20
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(99)
+    g = torch.zeros(N, dtype=torch.float32, device=DEV)
+    g[N - R:] = torch.randn(R, dtype=torch.float32, device=DEV, generator=gen)
+    region = g[N - R:].cpu().numpy()
+    K = R // 100
+    sel = pipeline.DeftSelector([N], 1, K / N, DEV, out_cap=K + 8)
+    gi, gv = sel.topk_global(g, K)
+    stats = _first_pass_stats(sel)
+    oi, ov = O.topk_global(region, K)
+    assert (gi.astype(np.int64) == oi + (N - R)).all()
+    assert (_bits(gv) == _bits(ov)).all()
+    assert stats == [1, 0, 0], stats
+    del g
+    torch.cuda.empty_cache()
+
+
 def test_calls_can_be_captured_in_a_hip_graph(deft):
     """The device entry points only launch kernels on the given stream (no allocation, no
     memset, no synchronisation), so a caller may record them in a HIP graph.  The graph is
@@ -829,3 +854,45 @@ def test_calls_can_be_captured_in_a_hip_graph(deft):
         assert idx.tolist() == o_idx.tolist()
         assert (_bits(val) == _bits(o_val)).all()
         _check_norms(norms, O.layer_norms(g_host, off))
+
+
+def test_sampled_one_read_path_can_be_captured_in_a_hip_graph(deft):
+    """topk_global through the long-vector kernels with sampling (set-up, sampling, placement,
+    the one read, the check, the launches that back it up, the slot kernels, the ordered write:
+    kernels only) recorded in a HIP graph and replayed on changing data, with eager work between
+    the replays; every replay against the oracle, and the diagnostics words say which way the
+    first pass went (the third data set is built to mislead the sample, so that replay takes the
+    two-read path inside the same graph)."""
+    N = 8_000_000
+    rng = np.random.default_rng(5)
+    base = rng.standard_normal(N).astype(np.float32)
+    K = 80_000
+    sel = _sampled_selector([N])
+    gd = torch.from_numpy(base).to(DEV)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        deft.topk_global(gd, K, sel.idx_out, sel.val_out, sel.ws, stream=torch.cuda.current_stream(),
+                         shape=deft.SHAPE_LONG_SAMPLED)
+    pos = _sample_positions(0, N)
+    unseen = np.ones(N, bool)
+    unseen[pos] = False
+    for rep in range(4):
+        g_host = base * np.float32(1.0 + 0.5 * rep)
+        want = [1, 0, 0]
+        if rep == 2:  # large keys where the sample does not look: the check must refute the bound
+            hidden = rng.choice(np.nonzero(unseen)[0], 100_000, replace=False)
+            g_host = rng.uniform(-1e-3, 1e-3, N).astype(np.float32)
+            g_host[hidden] = rng.uniform(1.0, 2.0, hidden.size).astype(np.float32)
+            want = [0, 1, 0]
+        gd.copy_(torch.from_numpy(g_host))
+        sel.idx_out.zero_()                            # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        stats = _first_pass_stats(sel)
+        oi, ov = O.topk_global(g_host, K)
+        assert sel.idx_out[:K].cpu().numpy().tolist() == oi.tolist()
+        assert (_bits(sel.val_out[:K].cpu().numpy()) == _bits(ov)).all()
+        assert stats == want, (rep, stats)
