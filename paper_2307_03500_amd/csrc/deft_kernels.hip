@@ -18,6 +18,12 @@
 // A chunk whose slots overflowed is read from the segment again by the three slot kernels.
 // The bucket search between levels runs inside the next kernel (short vectors) or as a
 // one-workgroup-per-segment kernel (long vectors).
+// Long vectors read a qualifying segment ONCE: a 1/128 sample places the threshold's top digit
+// within four digits (sample_hist, bounds), the one full pass parks every key at or above the
+// lowest of them and histograms the four digits on their top 21 bits (pass1_bounded), and an
+// exact check of the counts (find_first) either yields the state after two digit levels or
+// sends the segment down the two-read path above.  The sample decides how often a segment is
+// read, never what is selected.
 // An element is selected iff key > T, or key == T and fewer than r equal keys precede it in
 // its segment.  Every pass walks the segments in fixed-size chunks; a chunk never spans two
 // segments, so small layers simply own short chunks and large layers are split over many
