@@ -54,6 +54,7 @@ constexpr uint32_t kStreamGrid = DEFT_STREAM_GRID;
 // Workgroups of the grid-stride third-level kernel of long vectors (measured on 1.42 GB: 24 / 17 /
 // 15 / 12.8 / 13 us with 512 / 768 / 1024 / 1536 / 2048).
 constexpr uint32_t kSlotWaveGrid = 2048;
+constexpr uint32_t kOverflowGrid = 2048;  // workgroups of the launch that writes overflowed chunks
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
@@ -307,6 +308,13 @@ struct SegDesc {
 //                 (find_first_kernel).
 //   kModeFailed:  the check failed (the sample misled): the segment is read again as kModeFull.
 constexpr uint32_t kModeFull = 0, kModeBounded = 1, kModeFailed = 2;
+// The one-read pass is taken where it would park at most one key in kParkDiv, the slots' share
+// of a chunk (beyond it most chunks would overflow their slots).  Conventional Top-k over 1.4 GB at
+// d = 0.05 / 0.1 / 0.2: 459 / 572 / 818 us read once, 682 / 814 / 1064 us read twice.
+#ifndef DEFT_PARK_DIV
+#define DEFT_PARK_DIV 4
+#endif
+constexpr uint32_t kParkDiv = DEFT_PARK_DIV;
 constexpr int kHiCopies = 16;
 struct SegBound {
   uint32_t mode;
@@ -320,6 +328,12 @@ struct SegBound {
 // Bits of the flag word the first bucket search leaves for the kernels behind it.
 constexpr uint32_t kFlagPass2 = 2u;   // some segment needs the full first pass and pass 2
 constexpr uint32_t kFlagLevel2 = 4u;  // some segment's threshold still lacks its last digit
+constexpr uint32_t kFlagOverflow = 8u;  // some chunk parked more keys than it has slots
+// Raised by whoever meets such a chunk, once per launch rather than once per chunk where chunks
+// overflow in their thousands (dense selections): atomics on one word are served one by one.
+__device__ __forceinline__ void raise_flag(uint32_t* flags, uint32_t bit) {
+  if (!(__hip_atomic_load(flags, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit)) atomicOr(flags, bit);
+}
 
 struct SegState {
   uint32_t prefix;  // key bits fixed so far (right-aligned)
@@ -874,7 +888,7 @@ __global__ __launch_bounds__(kThreads) void bounds_kernel(const SegDesc* __restr
   if (threadIdx.x == 0) {
     const uint32_t b_lo = res[0], at_or_above = res[1], b_hi = res[2];
     const bool ok = hi_thr <= n_s && lo_thr >= 1 && b_hi != 0xFFFFFFFFu && b_hi <= b_lo + 3 &&
-                    (uint64_t)at_or_above * 32u <= n_s;  // parks about 3 % of the segment at most
+                    (uint64_t)at_or_above * kParkDiv <= n_s;  // parks 1/kParkDiv of the segment at most
     bnd[j].mode = ok ? kModeBounded : kModeFull;
     bnd[j].b_lo = b_lo;
     if (!ok) atomicOr(flags, kFlagPass2);
@@ -1044,28 +1058,45 @@ __device__ __forceinline__ void load_batch(VecBatch& b, const float* __restrict_
 // pass once the candidates are a few per cent of the keys (a wavefront instruction occupies its
 // SIMD for four cycles, which at full memory rate leaves about twenty of them per element on the
 // whole chip).
-constexpr uint32_t kStageCap = 2 * kMaxSlotCap;  // the slot capacity of the long-vector shape
+#ifndef DEFT_LONG_CAP_MULT
+#define DEFT_LONG_CAP_MULT 8
+#endif
+#ifndef DEFT_STAGE_MULT
+#define DEFT_STAGE_MULT 2
+#endif
+constexpr uint32_t kLongSlotCap = DEFT_LONG_CAP_MULT * kMaxSlotCap;  // the slot capacity of the long-vector shape
+// Entries a wavefront of the bounded first pass holds in LDS before it moves them to the slots: a
+// step adds 256 at most, so the staging array is emptied whenever fewer than that are free.
+constexpr uint32_t kStageCap = DEFT_STAGE_MULT * kMaxSlotCap;
+static_assert(kStageCap >= 512, "a step of the walk may park 256 entries");
 template <int HITERS, bool INTERIOR>
 __device__ __forceinline__ uint32_t park_chunk(const float* __restrict__ g, int64_t at, int64_t s,
                                                int64_t e, uint32_t lo_key, uint32_t* __restrict__ lh,
-                                               uint2* __restrict__ stage, uint2* __restrict__ my_slots) {
+                                               uint2* __restrict__ stage, uint2* __restrict__ my_slots,
+                                               uint32_t cap) {
   constexpr int kBinsB = 1 << kBitsB;
   constexpr int kShift = kBits1 + kBits2;
   constexpr int kBatches = HITERS / kBatchVecs;
   const int lane = threadIdx.x & 63;
   const unsigned long long below = (1ull << lane) - 1ull;
-  uint32_t filled = 0;
+  uint32_t filled = 0;   // entries parked so far
+  uint32_t flushed = 0;  // of which have left the staging array
+  uint32_t low_set = 0;
   auto bin_of = [&](uint32_t rawv) {
     const uint32_t rel = (rawv & 0x7FFFFFFFu) - lo_key;
     return rel < (4u << kShift) ? (rel >> kBits2) : (uint32_t)kBinsB;
   };
-  auto one = [&](uint32_t rawv, uint32_t idx, uint32_t pos) {
-    if (pos < kStageCap) {
-      stage[pos] = make_uint2(rawv, idx);
-    } else {  // beyond the slots: counted, not kept
-      atomicAdd(&lh[bin_of(rawv)], 1u);
-      if (rawv & ((1u << kBits2) - 1u)) atomicAdd(&lh[kBinsB + 2], 1u);
+  auto one = [&](uint32_t rawv, uint32_t idx, uint32_t pos) { stage[pos - flushed] = make_uint2(rawv, idx); };
+  // The staged entries (written and read by this wavefront only) leave for the slots, every lane
+  // busy: dense stores, and the histogram update.  Entries beyond the slots are counted, not kept.
+  auto flush = [&]() {
+    for (uint32_t r = lane; r < filled - flushed; r += 64) {
+      const uint2 en = stage[r];
+      if (flushed + r < cap) my_slots[flushed + r] = en;
+      atomicAdd(&lh[bin_of(en.x)], 1u);
+      low_set += (en.x & ((1u << kBits2) - 1u)) ? 1u : 0u;
     }
+    flushed = filled;
   };
   auto park = [&](const VecBatch& B, int t0) {
 #pragma unroll
@@ -1078,6 +1109,7 @@ __device__ __forceinline__ uint32_t park_chunk(const float* __restrict__ g, int6
       const bool any = l[0] || l[1] || l[2] || l[3];
       const unsigned long long anyb = __ballot(any);
       if (anyb == 0ull) continue;
+      if (filled - flushed > kStageCap - 256u) flush();  // room for whatever this step parks
       const uint32_t idx0 = (uint32_t)(at + (int64_t)(t0 + i) * 256);
       const uint32_t cnt = (uint32_t)l[0] + (uint32_t)l[1] + (uint32_t)l[2] + (uint32_t)l[3];
       if (__ballot(cnt > 1u) == 0ull) {
@@ -1122,15 +1154,7 @@ __device__ __forceinline__ uint32_t park_chunk(const float* __restrict__ g, int6
       park(bufA, bt * kBatchVecs);
     }
   }
-  // the staged entries (written and read by this wavefront only) leave for the slots
-  const uint32_t kept = min(filled, kStageCap);
-  uint32_t low_set = 0;
-  for (uint32_t r = lane; r < kept; r += 64) {
-    const uint2 en = stage[r];
-    my_slots[r] = en;
-    atomicAdd(&lh[bin_of(en.x)], 1u);
-    low_set += (en.x & ((1u << kBits2) - 1u)) ? 1u : 0u;
-  }
+  flush();
   // how many parked keys have any of their low kBits2 bits set: if none has (gradients that
   // went through a 16-bit format), the 21 bits resolved by this pass are the whole key
   if (__ballot(low_set != 0) != 0ull) {
@@ -1174,8 +1198,8 @@ __global__ __launch_bounds__(kThreads) void pass1_bounded_kernel(
   const uint32_t ec_local = local * 4 + wave;  // this wave's count/emit chunk
   uint2* my_slots = slots + (size_t)(d.chunk_base + ec_local) * cap;
   const uint32_t filled = (cstart >= s && cstart + kElems <= e)
-                              ? park_chunk<HITERS, true>(g, at, s, e, lo_key, lh, stage[wave], my_slots)
-                              : park_chunk<HITERS, false>(g, at, s, e, lo_key, lh, stage[wave], my_slots);
+                              ? park_chunk<HITERS, true>(g, at, s, e, lo_key, lh, stage[wave], my_slots, cap)
+                              : park_chunk<HITERS, false>(g, at, s, e, lo_key, lh, stage[wave], my_slots, cap);
   if (lane == 0) {
     if (ec_local < n_chunks) live_cnt[d.chunk_base + ec_local] = filled;
     if (filled) lh[kBinsB + 1] = 1u;
@@ -1414,7 +1438,7 @@ __global__ __launch_bounds__(kThreads) void slot_count_kernel(
     const float* __restrict__ g, const SegDesc* __restrict__ seg, SegState* __restrict__ st, int m,
     const uint32_t* __restrict__ hist, const uint32_t* __restrict__ live_cnt,
     const uint2* __restrict__ slots, uint32_t cap, uint32_t* __restrict__ chunk_gt,
-    uint32_t* __restrict__ chunk_eq) {
+    uint32_t* __restrict__ chunk_eq, uint32_t* __restrict__ flags) {
   __shared__ uint32_t red[2 * kWaves];
   __shared__ uint32_t fl[kWaves + 8];
   const int j = seg_of_chunk(seg, m, blockIdx.x);
@@ -1435,6 +1459,7 @@ __global__ __launch_bounds__(kThreads) void slot_count_kernel(
       eq = key == T ? 1u : 0u;
     }
   } else {
+    if (threadIdx.x == 0) raise_flag(flags, kFlagOverflow);  // the ordered write needs its second launch
     Chunk<ITERS> ch;
     ch.load(g, d.start, (int64_t)d.start + d.size, local);
 #pragma unroll
@@ -1576,7 +1601,7 @@ __global__ __launch_bounds__(kThreads) void slot_count_wave_kernel(
     const float* __restrict__ g, const SegDesc* __restrict__ seg, const SegState* __restrict__ st,
     int m, uint32_t chunks, const uint32_t* __restrict__ live_cnt,
     const uint2* __restrict__ slots, uint32_t cap, uint32_t* __restrict__ chunk_gt,
-    uint32_t* __restrict__ chunk_eq) {
+    uint32_t* __restrict__ chunk_eq, uint32_t* __restrict__ flags) {
   __shared__ uint32_t red[2 * kWaves];
   __shared__ uint32_t ovf[kWaves];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -1613,6 +1638,7 @@ __global__ __launch_bounds__(kThreads) void slot_count_wave_kernel(
     const int j = seg_of_chunk(seg, m, cq);
     const SegDesc d = seg[j];
     const uint32_t T = st[(size_t)3 * m + j].T;
+    if (threadIdx.x == 0) raise_flag(flags, kFlagOverflow);
     Chunk<ITERS> ch;
     ch.load(g, d.start, (int64_t)d.start + d.size, cq - d.chunk_base);
     uint32_t gt = 0, eq = 0;
@@ -1779,40 +1805,49 @@ __device__ __forceinline__ void emit_from_segment(
 // are granted in index order until the quota r is used up, so a chunk's first output slot is
 // out_off + (keys > T before it) + min(r, keys == T before it)  within its segment.  SCAN_HERE:
 // the workgroup sums the counts of the preceding chunks of its segment itself -- cheaper than a
-// scan launch when every segment is short.  The chunk's selectable keys come from its slots (parked by pass 2
-// in index order, one thread per entry); only a chunk that overflowed its slots is read from
-// the segment again.
-template <int ITERS, bool SCAN_HERE>
-__global__ __launch_bounds__(kThreads) void emit_kernel(
-    const float* __restrict__ g, const SegDesc* __restrict__ seg, const SegState* __restrict__ st,
-    int m, const uint32_t* __restrict__ chunk_gt, const uint32_t* __restrict__ chunk_eq,
+// scan launch when every segment is short; otherwise tile-local prefixes from scan_tiles_kernel
+// plus the totals of the tiles in between.
+struct WriteBase {
+  SegDesc d;
+  uint32_t T, r;      // threshold key, ties to take
+  uint32_t cgt, ceq;  // the chunk's keys above / at the threshold
+  uint32_t eb, ob;    // ties in the segment's earlier chunks; the chunk's first output position
+  bool any;           // the chunk writes something
+};
+
+template <bool SCAN_HERE>
+__device__ __forceinline__ WriteBase write_base(
+    uint32_t c, const SegDesc* __restrict__ seg, const SegState* __restrict__ st, int m,
+    const uint32_t* __restrict__ chunk_gt, const uint32_t* __restrict__ chunk_eq,
     const uint32_t* __restrict__ pre_gt, const uint32_t* __restrict__ pre_eq,
     const uint32_t* __restrict__ tile_gt, const uint32_t* __restrict__ tile_eq,
-    const uint32_t* __restrict__ live_cnt, const uint2* __restrict__ slots, uint32_t cap,
-    int32_t* __restrict__ idx_out, float* __restrict__ val_out) {
-  __shared__ uint32_t wtot[2][kWaves];
-  const int j = seg_of_chunk(seg, m, blockIdx.x);
-  const SegDesc d = seg[j];
-  const uint32_t T = st[(size_t)3 * m + j].T, r = st[(size_t)3 * m + j].r;
+    uint32_t (*wtot)[kWaves]) {
+  WriteBase w;
+  const int j = seg_of_chunk(seg, m, c);
+  w.d = seg[j];
+  w.T = st[(size_t)3 * m + j].T;
+  w.r = st[(size_t)3 * m + j].r;
+  w.cgt = chunk_gt[c];
+  w.ceq = chunk_eq[c];
+  w.eb = 0;
+  w.ob = 0;
+  w.any = false;
   // a chunk that holds nothing to select is not read at all
-  const uint32_t cgt = chunk_gt[blockIdx.x], ceq = chunk_eq[blockIdx.x];
-  if (cgt == 0 && ceq == 0) return;
-  // counts in the segment's earlier chunks: summed here (short segments), or tile-local prefixes
-  // from scan_tiles_kernel plus the totals of the tiles in between
+  if (w.cgt == 0 && w.ceq == 0) return w;
   uint32_t sg = 0, se = 0;
   if (SCAN_HERE) {
-    for (uint32_t c = d.chunk_base + threadIdx.x; c < blockIdx.x; c += kThreads) {
-      sg += chunk_gt[c];
-      se += chunk_eq[c];
+    for (uint32_t i = w.d.chunk_base + threadIdx.x; i < c; i += kThreads) {
+      sg += chunk_gt[i];
+      se += chunk_eq[i];
     }
   } else {
-    for (uint32_t t = d.chunk_base / kScanTile + threadIdx.x; t < blockIdx.x / kScanTile; t += kThreads) {
+    for (uint32_t t = w.d.chunk_base / kScanTile + threadIdx.x; t < c / kScanTile; t += kThreads) {
       sg += tile_gt[t];
       se += tile_eq[t];
     }
     if (threadIdx.x == 0) {
-      sg += pre_gt[blockIdx.x] - pre_gt[d.chunk_base];
-      se += pre_eq[blockIdx.x] - pre_eq[d.chunk_base];
+      sg += pre_gt[c] - pre_gt[w.d.chunk_base];
+      se += pre_eq[c] - pre_eq[w.d.chunk_base];
     }
   }
   sg = wave_sum_u32(sg);
@@ -1820,22 +1855,40 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(
   if ((threadIdx.x & 63) == 0) { wtot[0][threadIdx.x >> 6] = sg; wtot[1][threadIdx.x >> 6] = se; }
   __syncthreads();
   const uint32_t gt_before = wtot[0][0] + wtot[0][1] + wtot[0][2] + wtot[0][3];
-  const uint32_t eb = wtot[1][0] + wtot[1][1] + wtot[1][2] + wtot[1][3];
-  const uint32_t ob = d.out_off + gt_before + min(r, eb);
+  w.eb = wtot[1][0] + wtot[1][1] + wtot[1][2] + wtot[1][3];
+  w.ob = w.d.out_off + gt_before + min(w.r, w.eb);
   __syncthreads();
-  if (cgt == 0 && eb >= r) return;  // only ties here, and the quota was used up before them
-  const int mode = (eb >= r) ? 0 : ((r - eb >= ceq) ? 1 : 2);
+  // (only ties here, and the quota used up before them: nothing to write)
+  w.any = !(w.cgt == 0 && w.eb >= w.r);
+  return w;
+}
+
+// The chunk's selectable keys come from its slots (parked in index order, one thread per
+// entry).  A chunk that overflowed its slots is left to emit_overflow_kernel: reading it from the
+// segment here would cost every workgroup of this kernel the registers of that rare path, and
+// with them half the wavefronts a SIMD can hold (26.5 -> 15 us on the BERT-shaped conventional
+// Top-k with the path split off).
+template <int ITERS, bool SCAN_HERE>
+__global__ __launch_bounds__(kThreads) void emit_kernel(
+    const SegDesc* __restrict__ seg, const SegState* __restrict__ st,
+    int m, const uint32_t* __restrict__ chunk_gt, const uint32_t* __restrict__ chunk_eq,
+    const uint32_t* __restrict__ pre_gt, const uint32_t* __restrict__ pre_eq,
+    const uint32_t* __restrict__ tile_gt, const uint32_t* __restrict__ tile_eq,
+    const uint32_t* __restrict__ live_cnt, const uint2* __restrict__ slots, uint32_t cap,
+    int32_t* __restrict__ idx_out, float* __restrict__ val_out) {
+  __shared__ uint32_t wtot[2][kWaves];
+  const WriteBase w = write_base<SCAN_HERE>(blockIdx.x, seg, st, m, chunk_gt, chunk_eq, pre_gt, pre_eq,
+                                            tile_gt, tile_eq, wtot);
+  if (!w.any) return;
+  const uint32_t T = w.T, r = w.r;
+  const int mode = (w.eb >= r) ? 0 : ((r - w.eb >= w.ceq) ? 1 : 2);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const uint32_t lim = d.out_off + d.k;  // a segment never writes past its own k slots
+  const uint32_t lim = w.d.out_off + w.d.k;  // a segment never writes past its own k slots
   const uint32_t n_live = live_cnt[blockIdx.x];
-  if (n_live > cap) {
-    emit_from_segment<ITERS>(g, d, blockIdx.x - d.chunk_base, T, r, eb, ob, mode, lim, idx_out,
-                             val_out, wtot);
-    return;
-  }
+  if (n_live > cap) return;
   // entries in index order, kThreads at a time (one round unless the cap exceeds the workgroup)
   const unsigned long long below = (1ull << lane) - 1ull;
-  uint32_t pos_base = ob, rank_base = eb;
+  uint32_t pos_base = w.ob, rank_base = w.eb;
   for (uint32_t r0 = 0; r0 < n_live; r0 += kThreads) {
     const bool on = r0 + threadIdx.x < n_live;
     const uint2 e = on ? slots[(size_t)blockIdx.x * cap + r0 + threadIdx.x] : make_uint2(0u, 0u);
@@ -1849,7 +1902,7 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(
       if (lane == 0) wtot[1][wave] = (uint32_t)__popcll(eqb);
       __syncthreads();
       uint32_t rank = rank_base + (uint32_t)__popcll(eqb & below);
-      for (int w = 0; w < wave; ++w) rank += wtot[1][w];
+      for (int w2 = 0; w2 < wave; ++w2) rank += wtot[1][w2];
       take = take || (is_eq && rank < r);
       rank_base += wtot[1][0] + wtot[1][1] + wtot[1][2] + wtot[1][3];
     }
@@ -1857,7 +1910,7 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(
     if (lane == 0) wtot[0][wave] = (uint32_t)__popcll(tb);
     __syncthreads();
     uint32_t pos = pos_base + (uint32_t)__popcll(tb & below);
-    for (int w = 0; w < wave; ++w) pos += wtot[0][w];
+    for (int w2 = 0; w2 < wave; ++w2) pos += wtot[0][w2];
     if (take && pos < lim) {
       idx_out[pos] = (int32_t)e.y;
       val_out[pos] = __uint_as_float(e.x);
@@ -1867,96 +1920,97 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(
   }
 }
 
+// The chunks that overflowed their slots (heavy ties, dense selections), written from the
+// segment itself.  Launched behind every ordered write; a no-op unless the count kernel met such
+// a chunk and raised kFlagOverflow.  A fixed set of workgroups strides over the chunks.
+template <int ITERS, bool SCAN_HERE>
+__global__ __launch_bounds__(kThreads) void emit_overflow_kernel(
+    const float* __restrict__ g, const SegDesc* __restrict__ seg, const SegState* __restrict__ st,
+    int m, uint32_t chunks, const uint32_t* __restrict__ chunk_gt,
+    const uint32_t* __restrict__ chunk_eq, const uint32_t* __restrict__ pre_gt,
+    const uint32_t* __restrict__ pre_eq, const uint32_t* __restrict__ tile_gt,
+    const uint32_t* __restrict__ tile_eq, const uint32_t* __restrict__ live_cnt, uint32_t cap,
+    const uint32_t* __restrict__ flags, int32_t* __restrict__ idx_out, float* __restrict__ val_out) {
+  __shared__ uint32_t wtot[2][kWaves];
+  if (!(*flags & kFlagOverflow)) return;
+  for (uint32_t c = blockIdx.x; c < chunks; c += gridDim.x) {
+    if (live_cnt[c] <= cap) continue;
+    const WriteBase w = write_base<SCAN_HERE>(c, seg, st, m, chunk_gt, chunk_eq, pre_gt, pre_eq, tile_gt,
+                                              tile_eq, wtot);
+    if (w.any) {
+      const int mode = (w.eb >= w.r) ? 0 : ((w.r - w.eb >= w.ceq) ? 1 : 2);
+      emit_from_segment<ITERS>(g, w.d, c - w.d.chunk_base, w.T, w.r, w.eb, w.ob, mode,
+                               w.d.out_off + w.d.k, idx_out, val_out, wtot);
+    }
+    __syncthreads();  // wtot is reused from one chunk to the next
+  }
+}
+
 // The same for long vectors: one wavefront per chunk, so that the many chunks that hold nothing
 // cost a wavefront's two loads instead of a workgroup (32 -> 17 us on a 1.4 GB vector, where
 // three quarters of the chunks are empty); chunk prefixes come from scan_tiles_kernel
-// (tile-local prefixes and tile totals; a segment's own prefix is a difference).  Chunks
-// that overflowed their slots are then handled by the whole workgroup, one at a time.
-template <int ITERS>
+// (tile-local prefixes and tile totals; a segment's own prefix is a difference).  No barrier, no
+// LDS: a wavefront leaves as soon as its chunk is done.  Chunks that overflowed their slots are
+// left to emit_overflow_kernel.
 __global__ __launch_bounds__(kThreads) void emit_wave_kernel(
-    const float* __restrict__ g, const SegDesc* __restrict__ seg, const SegState* __restrict__ st,
+    const SegDesc* __restrict__ seg, const SegState* __restrict__ st,
     int m, uint32_t chunks, const uint32_t* __restrict__ chunk_gt,
     const uint32_t* __restrict__ chunk_eq, const uint32_t* __restrict__ pre_gt,
     const uint32_t* __restrict__ pre_eq, const uint32_t* __restrict__ tile_gt,
     const uint32_t* __restrict__ tile_eq, const uint32_t* __restrict__ live_cnt,
     const uint2* __restrict__ slots, uint32_t cap, int32_t* __restrict__ idx_out,
     float* __restrict__ val_out) {
-  __shared__ uint32_t wtot[2][kWaves];
-  __shared__ uint32_t ovf[kWaves], ovf_eb[kWaves], ovf_ob[kWaves];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint32_t c = blockIdx.x * kWaves + wave;
-  bool over = false;
-  uint32_t eb = 0, ob = 0;
-  if (c < chunks) {
-    // everything that is indexed by the chunk alone is fetched at once, ahead of the chain
-    // segment -> state -> prefixes -> slots (each link a round trip to memory)
-    const uint32_t cgt = chunk_gt[c], ceq = chunk_eq[c];
-    const uint32_t pg = pre_gt[c], pe = pre_eq[c], n = live_cnt[c];
-    const uint2 first = (n != 0 && n <= cap && (uint32_t)lane < n) ? slots[(size_t)c * cap + lane]
-                                                                 : make_uint2(0u, 0u);
-    if (cgt != 0 || ceq != 0) {
-      const int j = seg_of_chunk(seg, m, c);
-      const SegDesc d = seg[j];
-      const uint32_t T = st[(size_t)3 * m + j].T, r = st[(size_t)3 * m + j].r;
-      // prefix inside the segment: tile-local prefixes plus the totals of the tiles between the
-      // segment's first chunk and this one (few: a tile spans 2048 chunks), summed by the lanes
-      const uint32_t c0 = d.chunk_base;
-      uint32_t sg = 0, se = 0;
-      for (uint32_t t = c0 / kScanTile + lane; t < c / kScanTile; t += 64) {
-        sg += tile_gt[t];
-        se += tile_eq[t];
-      }
-      sg = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_sum_u32(sg));
-      se = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_sum_u32(se));
-      const uint32_t gt_before = sg + pg - pre_gt[c0];
-      eb = se + pe - pre_eq[c0];
-      ob = d.out_off + gt_before + min(r, eb);
-      if (!(cgt == 0 && eb >= r)) {
-        if (n > cap) {
-          over = true;
-        } else {
-          const int mode = (eb >= r) ? 0 : ((r - eb >= ceq) ? 1 : 2);
-          const uint32_t lim = d.out_off + d.k;
-          const unsigned long long below = (1ull << lane) - 1ull;
-          uint32_t pos = ob, rank = eb;
-          for (uint32_t r0 = 0; r0 < n; r0 += 64) {
-            const bool on = r0 + lane < n;
-            const uint2 e = r0 == 0 ? first : (on ? slots[(size_t)c * cap + r0 + lane] : make_uint2(0u, 0u));
-            const uint32_t key = e.x & 0x7FFFFFFFu;
-            const bool is_eq = on && key == T;
-            bool take = on && key > T;
-            if (mode == 1) {
-              take = take || is_eq;
-            } else if (mode == 2) {
-              const unsigned long long eqb = __ballot(is_eq);
-              take = take || (is_eq && rank + (uint32_t)__popcll(eqb & below) < r);
-              rank += (uint32_t)__popcll(eqb);
-            }
-            const unsigned long long tb = __ballot(take);
-            const uint32_t p = pos + (uint32_t)__popcll(tb & below);
-            if (take && p < lim) {
-              idx_out[p] = (int32_t)e.y;
-              val_out[p] = __uint_as_float(e.x);
-            }
-            pos += (uint32_t)__popcll(tb);
-          }
-        }
-      }
-    }
+  if (c >= chunks) return;
+  // everything that is indexed by the chunk alone is fetched at once, ahead of the chain
+  // segment -> state -> prefixes -> slots (each link a round trip to memory)
+  const uint32_t cgt = chunk_gt[c], ceq = chunk_eq[c];
+  const uint32_t pg = pre_gt[c], pe = pre_eq[c], n = live_cnt[c];
+  const uint2 first = (n != 0 && n <= cap && (uint32_t)lane < n) ? slots[(size_t)c * cap + lane]
+                                                               : make_uint2(0u, 0u);
+  if ((cgt == 0 && ceq == 0) || n > cap) return;
+  const int j = seg_of_chunk(seg, m, c);
+  const SegDesc d = seg[j];
+  const uint32_t T = st[(size_t)3 * m + j].T, r = st[(size_t)3 * m + j].r;
+  // prefix inside the segment: tile-local prefixes plus the totals of the tiles between the
+  // segment's first chunk and this one (few: a tile spans 2048 chunks), summed by the lanes
+  const uint32_t c0 = d.chunk_base;
+  uint32_t sg = 0, se = 0;
+  for (uint32_t t = c0 / kScanTile + lane; t < c / kScanTile; t += 64) {
+    sg += tile_gt[t];
+    se += tile_eq[t];
   }
-  if (lane == 0) { ovf[wave] = over ? 1u : 0u; ovf_eb[wave] = eb; ovf_ob[wave] = ob; }
-  __syncthreads();
-  for (int q = 0; q < kWaves; ++q) {
-    if (!ovf[q]) continue;
-    const uint32_t cq = blockIdx.x * kWaves + q;
-    const int j = seg_of_chunk(seg, m, cq);
-    const SegDesc d = seg[j];
-    const uint32_t T = st[(size_t)3 * m + j].T, r = st[(size_t)3 * m + j].r;
-    const uint32_t ebq = ovf_eb[q], obq = ovf_ob[q], ceq = chunk_eq[cq];
-    const int mode = (ebq >= r) ? 0 : ((r - ebq >= ceq) ? 1 : 2);
-    __syncthreads();  // wtot is reused from one overflowed chunk to the next
-    emit_from_segment<ITERS>(g, d, cq - d.chunk_base, T, r, ebq, obq, mode, d.out_off + d.k, idx_out,
-                             val_out, wtot);
+  sg = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_sum_u32(sg));
+  se = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_sum_u32(se));
+  const uint32_t gt_before = sg + pg - pre_gt[c0];
+  const uint32_t eb = se + pe - pre_eq[c0];
+  const uint32_t ob = d.out_off + gt_before + min(r, eb);
+  if (cgt == 0 && eb >= r) return;
+  const int mode = (eb >= r) ? 0 : ((r - eb >= ceq) ? 1 : 2);
+  const uint32_t lim = d.out_off + d.k;
+  const unsigned long long below = (1ull << lane) - 1ull;
+  uint32_t pos = ob, rank = eb;
+  for (uint32_t r0 = 0; r0 < n; r0 += 64) {
+    const bool on = r0 + lane < n;
+    const uint2 e = r0 == 0 ? first : (on ? slots[(size_t)c * cap + r0 + lane] : make_uint2(0u, 0u));
+    const uint32_t key = e.x & 0x7FFFFFFFu;
+    const bool is_eq = on && key == T;
+    bool take = on && key > T;
+    if (mode == 1) {
+      take = take || is_eq;
+    } else if (mode == 2) {
+      const unsigned long long eqb = __ballot(is_eq);
+      take = take || (is_eq && rank + (uint32_t)__popcll(eqb & below) < r);
+      rank += (uint32_t)__popcll(eqb);
+    }
+    const unsigned long long tb = __ballot(take);
+    const uint32_t p = pos + (uint32_t)__popcll(tb & below);
+    if (take && p < lim) {
+      idx_out[p] = (int32_t)e.y;
+      val_out[p] = __uint_as_float(e.x);
+    }
+    pos += (uint32_t)__popcll(tb);
   }
 }
 
@@ -1983,15 +2037,15 @@ inline int chunk_iters_for(int64_t elems, int32_t shape) {
 }
 // Whether a segment of a long vector is sampled ahead of its first pass: it must be long enough
 // for the sample (1/128 of it) to be cheap next to a second read, sparse enough for its
-// candidates to fit the per-chunk slots, and k/128 large enough for the sample to place the
-// threshold within two top digits.  DEFT_SHAPE_LONG_SAMPLED samples whatever can be sampled
+// candidates to fit the per-chunk slots on average, and k/128 large enough for the sample to
+// place the threshold within four top digits.  DEFT_SHAPE_LONG_SAMPLED samples whatever can be sampled
 // (the device side still turns down what its sample cannot place).
 constexpr uint32_t kSampleMinElems = 1u << 22;
 constexpr uint32_t kSampleMinK = 12800;
 inline bool sample_segment(const SegDesc& d, int32_t shape) {
   if (shape == DEFT_SHAPE_LONG_PLAIN || sample_pieces(d.start, d.size) == 0) return false;
   if (shape == DEFT_SHAPE_LONG_SAMPLED) return true;
-  return d.size >= kSampleMinElems && d.k >= kSampleMinK && (uint64_t)d.k * 32u <= d.size;
+  return d.size >= kSampleMinElems && d.k >= kSampleMinK && (uint64_t)d.k * kParkDiv <= d.size;
 }
 
 struct SelectLayout {
@@ -2002,13 +2056,15 @@ struct SelectLayout {
 // expected picks, 32..256): the conventional Top-k then overflowed in most chunks that hold
 // picks at all, because its picks sit in the few layers of large norm at many times the average
 // density.  The slot arrays are written sparsely, so the largest cap costs address space only.
-// Long vectors walk chunks twice as large and get twice the slots per chunk: the same address
-// space per element, and their slot kernels loop over the entries anyway.
+// Long vectors walk chunks twice as large with eight times the slots (a quarter of a chunk, 2 bytes
+// of address space per element): at 512 slots the BERT-shaped conventional Top-k (K = N/100)
+// overflowed in 840 .. 2000 of its 13365 chunks, each then read again from the segment by every
+// kernel behind the first pass (178 us; 158 us with 1024 slots, 148 us with 2048).
 inline uint32_t slot_cap_for(uint64_t /*total_k*/, uint64_t /*share*/, uint32_t chunk_elems) {
-  return kMaxSlotCap * (chunk_elems / (kThreads * 4 * DEFT_SEL_ITERS_SMALL));
+  return chunk_elems == kThreads * 4 * DEFT_SEL_ITERS_SMALL ? kMaxSlotCap : kLongSlotCap;
 }
 
-SelectLayout select_layout(int64_t m, uint64_t chunks, uint32_t cap = kMaxSlotCap) {
+SelectLayout select_layout(int64_t m, uint64_t chunks, uint32_t cap = std::max(kMaxSlotCap, kLongSlotCap / 2)) {
   SelectLayout w;
   size_t o = 0;
   w.stats = o; o = 256;  // DEFT_STAT_ words, at the very start of the workspace
@@ -2053,7 +2109,7 @@ int launch_select(const float* g, SegDesc* seg, SegState* st, int m, uint32_t ch
                   uint32_t hchunks, uint32_t* hist, uint32_t* cgt, uint32_t* ceq, uint32_t* obase,
                   uint32_t* ebase, uint32_t* tgt, uint32_t* teq, uint32_t* ccnt, uint32_t* hmax,
                   uint2* slots, SegBound* bnd, uint32_t* bhist, uint32_t sblocks, uint32_t* stats,
-                  uint32_t cap, bool scan_in_emit, bool dense, const SegBatch* inline_batch,
+                  uint32_t cap, bool scan_in_emit, const SegBatch* inline_batch,
                   int32_t* idx_out, float* val_out, hipStream_t s) {
   if constexpr (FUSED) {
     if (inline_batch)
@@ -2070,7 +2126,6 @@ int launch_select(const float* g, SegDesc* seg, SegState* st, int m, uint32_t ch
       // these are no-ops unless a segment was not sampled, turned down or refuted
       sample_hist_kernel<<<sblocks, kThreads, 0, s>>>(g, seg, m, hist);
       bounds_kernel<<<m, kThreads, 0, s>>>(seg, hist, bnd, flags);
-      if (cap != kStageCap) return DEFT_EINVAL;  // the staging arrays mirror the slots of this shape
       pass1_bounded_kernel<4 * ITERS><<<hchunks, kThreads, 0, s>>>(g, seg, m, bhist, bnd, ccnt, slots, cap);
       find_first_kernel<<<m, kThreads, 0, s>>>(st, m, seg, bhist, bnd, flags, stats);
     } else {
@@ -2084,30 +2139,34 @@ int launch_select(const float* g, SegDesc* seg, SegState* st, int m, uint32_t ch
                                                          FUSED ? nullptr : bnd,
                                                          FUSED ? nullptr : hmax + hchunks + 2);
   if (!FUSED) find_kernel<1><<<m, kThreads, 0, s>>>(st, m, hist, bnd, bnd ? hmax + hchunks + 2 : nullptr);
+  uint32_t* oflags = hmax + hchunks + 2;  // the flag word (cleared with the histograms)
   if (FUSED) {
     slot_hist2_kernel<ITERS, true><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist, ccnt, slots, cap);
     slot_count_kernel<ITERS, true><<<chunks, kThreads, 0, s>>>(g, seg, st, m, hist, ccnt, slots, cap,
-                                                              cgt, ceq);
+                                                              cgt, ceq, oflags);
   } else {
     const uint32_t wblocks = (chunks + kWaves - 1) / kWaves;
     slot_hist2_wave_kernel<ITERS><<<std::min<uint32_t>(wblocks, kSlotWaveGrid), kThreads, 0, s>>>(
         g, seg, st, m, chunks, hist, ccnt, slots, cap, bnd ? hmax + hchunks + 2 : nullptr);
     find_kernel<2><<<m, kThreads, 0, s>>>(st, m, hist, bnd, nullptr);
     slot_count_wave_kernel<ITERS><<<wblocks, kThreads, 0, s>>>(g, seg, st, m, chunks, ccnt, slots,
-                                                              cap, cgt, ceq);
+                                                              cap, cgt, ceq, oflags);
   }
+  // the ordered write from the slots, then (a no-op unless some chunk overflowed its slots) the
+  // overflowed chunks from the segments
+  const unsigned ogrid = std::min<uint32_t>(chunks, kOverflowGrid);
   if (scan_in_emit) {
-    emit_kernel<ITERS, true><<<chunks, kThreads, 0, s>>>(g, seg, st, m, cgt, ceq, obase, ebase, tgt, teq,
+    emit_kernel<ITERS, true><<<chunks, kThreads, 0, s>>>(seg, st, m, cgt, ceq, obase, ebase, tgt, teq,
                                                          ccnt, slots, cap, idx_out, val_out);
+    emit_overflow_kernel<ITERS, true><<<ogrid, kThreads, 0, s>>>(
+        g, seg, st, m, chunks, cgt, ceq, obase, ebase, tgt, teq, ccnt, cap, oflags, idx_out, val_out);
   } else {
     const uint32_t tiles = (chunks + kScanTile - 1) / kScanTile;
     scan_tiles_kernel<<<tiles, kThreads, 0, s>>>(cgt, ceq, chunks, obase, ebase, tgt, teq);
-    if (dense)  // most chunks hold many picks (and overflow their slots): a workgroup each
-      emit_kernel<ITERS, false><<<chunks, kThreads, 0, s>>>(g, seg, st, m, cgt, ceq, obase, ebase, tgt,
-                                                            teq, ccnt, slots, cap, idx_out, val_out);
-    else
-      emit_wave_kernel<ITERS><<<(chunks + kWaves - 1) / kWaves, kThreads, 0, s>>>(
-          g, seg, st, m, chunks, cgt, ceq, obase, ebase, tgt, teq, ccnt, slots, cap, idx_out, val_out);
+    emit_wave_kernel<<<(chunks + kWaves - 1) / kWaves, kThreads, 0, s>>>(
+        seg, st, m, chunks, cgt, ceq, obase, ebase, tgt, teq, ccnt, slots, cap, idx_out, val_out);
+    emit_overflow_kernel<ITERS, false><<<ogrid, kThreads, 0, s>>>(
+        g, seg, st, m, chunks, cgt, ceq, obase, ebase, tgt, teq, ccnt, cap, oflags, idx_out, val_out);
   }
   HIP_TRY(hipGetLastError());
   return DEFT_OK;
@@ -2170,13 +2229,6 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   uint64_t total_k = 0;
   for (const auto& d : segs) total_k += d.k;
   const uint32_t cap = slot_cap_for(total_k, (uint64_t)share, ce);
-  // More than a tenth of a slot array per chunk expected on average: the ordered write then
-  // takes a workgroup per chunk (measured on the BERT-shaped set, K = N/100, where a chunk holds
-  // about 80 picks: 26.7 us against 36.0 us with a wavefront per chunk).
-#ifndef DEFT_DENSE_FRAC
-#define DEFT_DENSE_FRAC 0.1
-#endif
-  const bool dense = (double)ce * (double)total_k > DEFT_DENSE_FRAC * cap * (double)share;
   const bool inline_segs = pre && small && m <= kSegBatch && m <= pre->m_cap && chunks <= pre->chunks_cap;
   const SelectLayout w = inline_segs ? select_layout(pre->m_cap, pre->chunks_cap, cap) : select_layout(m, chunks, cap);
   if (w.total > ws_bytes) return DEFT_EWS;
@@ -2221,11 +2273,11 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
   if (small)
     return launch_select<DEFT_SEL_ITERS_SMALL, true>(
         g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, tg, te, cc, hm, sl, nullptr,
-        nullptr, 0, nullptr, cap, scan_in_emit, dense, inline_segs ? &b : nullptr, idx_out, val_out, s);
+        nullptr, 0, nullptr, cap, scan_in_emit, inline_segs ? &b : nullptr, idx_out, val_out, s);
   return launch_select<DEFT_SEL_ITERS_LARGE, false>(
       g, seg, st, m, (uint32_t)chunks, (uint32_t)hchunks, hist, cgt, ceq, ob, eb, tg, te, cc, hm, sl, bnd,
       reinterpret_cast<uint32_t*>(base + w.bhist), (uint32_t)sblocks,
-      reinterpret_cast<uint32_t*>(base + w.stats), cap, scan_in_emit, dense, nullptr, idx_out, val_out, s);
+      reinterpret_cast<uint32_t*>(base + w.stats), cap, scan_in_emit, nullptr, idx_out, val_out, s);
 }
 
 }  // namespace

@@ -458,6 +458,37 @@ def test_sampled_first_pass_many_segments(deft):
             assert stats[0] == 2, stats   # the 13 M and the 3 M segment are read once
 
 
+def test_sampled_first_pass_crowded_chunks(deft):
+    """The one-read first pass on a segment whose large keys crowd into a few chunks of 8192:
+    counts around every boundary of its parking -- the staging array of a wavefront (emptied
+    into the slots when fewer than 256 places are free), the slots of a chunk (2048; a chunk
+    holding more is read again from the segment by the kernels behind the pass) and a chunk made
+    of large keys only -- with the tie class of the threshold spread over all of them."""
+    N = 16_000_037
+    rng = np.random.default_rng(36)
+    g = (rng.standard_normal(N) * 1e-3).astype(np.float32)
+    crowded = {3: 255, 10: 256, 11: 257, 40: 511, 41: 513, 90: 767, 91: 769, 200: 1025, 300: 2047,
+               301: 2048, 302: 2049, 500: 3000, 700: 8192, 1953: 8192 - 5}
+    n_big = 0
+    for chunk, count in crowded.items():
+        lo = chunk * 8192
+        hi = min(N, lo + 8192)
+        pos = lo + rng.choice(hi - lo, min(count, hi - lo), replace=False)
+        # large keys with few distinct values: ties at the threshold wherever it falls among them
+        g[pos] = ((1.0 + rng.integers(0, 6, len(pos)) * 0.125) * rng.choice([-1, 1], len(pos))).astype(np.float32)
+        n_big += len(pos)
+    sel = _sampled_selector([N])
+    gd = torch.from_numpy(g).to(DEV)
+    for K in (n_big - 3000, n_big, n_big + 40_000):
+        gi, gv = sel.topk_global(gd, K)
+        stats = _first_pass_stats(sel)
+        oi, ov = O.topk_global(g, K)
+        assert gi.tolist() == oi.tolist() and (_bits(gv) == _bits(ov)).all()
+        assert sum(stats) == 1 and stats[1] == 0, stats
+        if K > n_big:  # threshold among the small keys, where the sample places it: read once
+            assert stats == [1, 0, 0], stats
+
+
 @pytest.mark.parametrize("case", ["large_keys_hide_from_the_sample", "sample_sees_only_large_keys",
                                   "gaps_between_digits"])
 def test_sampled_first_pass_misled_sample_is_redone(deft, case):
