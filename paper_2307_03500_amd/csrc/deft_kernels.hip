@@ -1864,13 +1864,13 @@ __device__ __forceinline__ WriteBase write_base(
 }
 
 // The chunk's selectable keys come from its slots (parked in index order, one thread per
-// entry).  A chunk that overflowed its slots is left to emit_overflow_kernel: reading it from the
-// segment here would cost every workgroup of this kernel the registers of that rare path, and
-// with them half the wavefronts a SIMD can hold (26.5 -> 15 us on the BERT-shaped conventional
-// Top-k with the path split off).
-template <int ITERS, bool SCAN_HERE>
+// entry).  A chunk that overflowed its slots is read from the segment again: here (OVERFLOW_HERE:
+// short selections, where one more launch would cost more than the registers of that rare path),
+// or by emit_overflow_kernel (long vectors: the path costs every workgroup of the kernel its
+// registers and with them half the wavefronts a SIMD can hold).
+template <int ITERS, bool SCAN_HERE, bool OVERFLOW_HERE>
 __global__ __launch_bounds__(kThreads) void emit_kernel(
-    const SegDesc* __restrict__ seg, const SegState* __restrict__ st,
+    const float* __restrict__ g, const SegDesc* __restrict__ seg, const SegState* __restrict__ st,
     int m, const uint32_t* __restrict__ chunk_gt, const uint32_t* __restrict__ chunk_eq,
     const uint32_t* __restrict__ pre_gt, const uint32_t* __restrict__ pre_eq,
     const uint32_t* __restrict__ tile_gt, const uint32_t* __restrict__ tile_eq,
@@ -1885,7 +1885,12 @@ __global__ __launch_bounds__(kThreads) void emit_kernel(
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint32_t lim = w.d.out_off + w.d.k;  // a segment never writes past its own k slots
   const uint32_t n_live = live_cnt[blockIdx.x];
-  if (n_live > cap) return;
+  if (n_live > cap) {
+    if (OVERFLOW_HERE)
+      emit_from_segment<ITERS>(g, w.d, blockIdx.x - w.d.chunk_base, T, r, w.eb, w.ob, mode, lim, idx_out,
+                               val_out, wtot);
+    return;
+  }
   // entries in index order, kThreads at a time (one round unless the cap exceeds the workgroup)
   const unsigned long long below = (1ull << lane) - 1ull;
   uint32_t pos_base = w.ob, rank_base = w.eb;
@@ -2155,9 +2160,12 @@ int launch_select(const float* g, SegDesc* seg, SegState* st, int m, uint32_t ch
   // the ordered write from the slots, then (a no-op unless some chunk overflowed its slots) the
   // overflowed chunks from the segments
   const unsigned ogrid = std::min<uint32_t>(chunks, kOverflowGrid);
-  if (scan_in_emit) {
-    emit_kernel<ITERS, true><<<chunks, kThreads, 0, s>>>(seg, st, m, cgt, ceq, obase, ebase, tgt, teq,
-                                                         ccnt, slots, cap, idx_out, val_out);
+  if (scan_in_emit && FUSED) {
+    emit_kernel<ITERS, true, true><<<chunks, kThreads, 0, s>>>(g, seg, st, m, cgt, ceq, obase, ebase, tgt,
+                                                               teq, ccnt, slots, cap, idx_out, val_out);
+  } else if (scan_in_emit) {
+    emit_kernel<ITERS, true, false><<<chunks, kThreads, 0, s>>>(g, seg, st, m, cgt, ceq, obase, ebase, tgt,
+                                                                teq, ccnt, slots, cap, idx_out, val_out);
     emit_overflow_kernel<ITERS, true><<<ogrid, kThreads, 0, s>>>(
         g, seg, st, m, chunks, cgt, ceq, obase, ebase, tgt, teq, ccnt, cap, oflags, idx_out, val_out);
   } else {
