@@ -362,8 +362,8 @@ int deft_accumulate_sparsify(const deft_job* job, const float* e_dev, const floa
  *                         count = my_count
  *   DEFT_OP_TOPK_GLOBAL:  elems = N,            count ignored
  * Returns 0 for an unknown op or negative arguments.  Orders of magnitude: norms 16 bytes per
- * 4096 elements; selection about 2.1 KB per 4096 elements plus 48 KB per layer, most of it the
- * per-chunk slot arrays, of which a few hundred bytes per chunk are touched.
+ * 4096 elements; selection about 2 bytes per element plus 48 KB per layer and 4 MB, nearly all
+ * of it the per-chunk slot arrays, of which a few hundred bytes per chunk are touched.
  */
 size_t deft_workspace_bytes(int op, int64_t elems, int32_t count);
 
