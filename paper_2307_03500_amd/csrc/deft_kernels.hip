@@ -257,11 +257,17 @@ __global__ __launch_bounds__(kThreads) void gather_zero_kernel(float* __restrict
 }
 
 // One workgroup per layer adds the partials of the chunks the layer touches, in chunk order
-// per thread and a fixed tree across threads.
-__global__ __launch_bounds__(kThreads) void norm_finish_kernel(
+// per thread and a fixed order across threads.  1024 threads: the longest layer sets the time of
+// this launch, which sits between the norm pass and the host's plan (a 51 M-element layer is
+// 12 500 partials: 12 dependent rounds per thread instead of 49).
+#ifndef DEFT_FINISH_THREADS
+#define DEFT_FINISH_THREADS 1024
+#endif
+constexpr int kFinishThreads = DEFT_FINISH_THREADS;
+__global__ __launch_bounds__(kFinishThreads) void norm_finish_kernel(
     const int64_t* __restrict__ off, int64_t N, const double* __restrict__ head,
     const double* __restrict__ tail, double* __restrict__ sumsq) {
-  __shared__ double red[kWaves];
+  __shared__ double red[kFinishThreads / 64];
   const int l = blockIdx.x;
   const int64_t s = off[l], e = off[l + 1];
   if (e <= s || s < 0 || e > N) {
@@ -279,9 +285,15 @@ __global__ __launch_bounds__(kThreads) void norm_finish_kernel(
     return;
   }
   double a = 0.0;
-  for (int64_t b = b0 + 1 + threadIdx.x; b <= b1; b += kThreads) a += head[b];
-  const double t = block_sum(a, red);
-  if (threadIdx.x == 0) sumsq[l] = (first ? head[b0] : tail[b0]) + t;
+  for (int64_t b = b0 + 1 + threadIdx.x; b <= b1; b += kFinishThreads) a += head[b];
+  a = wave_sum(a);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = a;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = 0.0;
+    for (int w = 0; w < kFinishThreads / 64; ++w) t += red[w];
+    sumsq[l] = (first ? head[b0] : tail[b0]) + t;
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -2321,7 +2333,7 @@ int launch_norms(const float* g, const float* grad, float eta, float* acc, int64
     norm_chunks_kernel<true><<<chunks, kThreads, 0, s>>>(src, N, offsets_dev, L, head, tail, sumsq_dev);
   else
     norm_chunks_kernel<false><<<chunks, kThreads, 0, s>>>(src, N, offsets_dev, L, head, tail, sumsq_dev);
-  norm_finish_kernel<<<L, kThreads, 0, s>>>(offsets_dev, N, head, tail, sumsq_dev);
+  norm_finish_kernel<<<L, kFinishThreads, 0, s>>>(offsets_dev, N, head, tail, sumsq_dev);
   HIP_TRY(hipGetLastError());
   return DEFT_OK;
 }
