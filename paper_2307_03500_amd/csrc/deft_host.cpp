@@ -160,7 +160,8 @@ extern "C" int deft_alloc_k(const double* norms, const int64_t* sizes, int32_t L
     }
     int64_t k;
     if ((double)sizes[l] < k_temp) k = sizes[l];
-    else k = std::max<int64_t>(1, (int64_t)std::floor(k_temp));
+    else if (k_temp < 2.0) k = 1;     // max(1, floor(k_temp)), also for a k_remain gone negative
+    else k = (int64_t)k_temp;         // floor of a positive value below 2^31: truncation
     k_out[l] = k;
     k_remain -= k;
   }
