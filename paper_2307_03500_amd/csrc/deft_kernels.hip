@@ -1064,12 +1064,11 @@ __device__ __forceinline__ void load_batch(VecBatch& b, const float* __restrict_
 // The walk of one wavefront over its count/emit chunk.  The common step finds nothing to park
 // (four compares and a ballot); the next most common finds at most one key per lane (one ballot
 // places them); only a step in which some lane holds several takes the general three-ballot
-// prefix.  Parked entries go to a staging array in LDS first and leave it at the end of the walk,
-// 64 at a time: dense stores to the chunk's slots, and the histogram update with every lane busy
-// instead of once per sparse step.  The instruction count of the sparse steps is what bounds the
-// pass once the candidates are a few per cent of the keys (a wavefront instruction occupies its
-// SIMD for four cycles, which at full memory rate leaves about twenty of them per element on the
-// whole chip).
+// prefix.  Parked entries go to a staging array in LDS first and leave it when it is nearly full
+// and at the end of the walk, 64 at a time: dense stores to the chunk's slots, and the histogram
+// update with every lane busy instead of once per sparse step.  (A wavefront instruction
+// occupies its SIMD for four cycles, which at full memory rate leaves about twenty of them per
+// element on the whole chip.)
 #ifndef DEFT_LONG_CAP_MULT
 #define DEFT_LONG_CAP_MULT 8
 #endif
@@ -1813,7 +1812,7 @@ __device__ __forceinline__ void emit_from_segment(
   }
 }
 
-// Ordered compaction of one chunk per workgroup (short segments, and dense selections).  Ties
+// Ordered compaction of one chunk per workgroup (segments of at most 2048 chunks).  Ties
 // are granted in index order until the quota r is used up, so a chunk's first output slot is
 // out_off + (keys > T before it) + min(r, keys == T before it)  within its segment.  SCAN_HERE:
 // the workgroup sums the counts of the preceding chunks of its segment itself -- cheaper than a
