@@ -343,8 +343,9 @@ def long_vector_shape(request):
 @pytest.mark.parametrize("frac", [20, 3])
 def test_topk_global_dense_on_one_long_segment(deft, long_vector_shape, frac):
     """A dense conventional Top-k over a segment of more than 2048 long-shape chunks: the
-    workgroup-per-chunk ordered write with scanned chunk prefixes, from slot arrays holding more
-    entries than the workgroup has threads (K = N/20) and from the segment itself (K = N/3)."""
+    ordered write with scanned chunk prefixes, from slot arrays holding several rounds of entries
+    per wavefront (K = N/20) and, for chunks that overflow their 2048 slots, from the segment
+    itself by the launch behind the ordered write (K = N/3)."""
     N = 2049 * 8192 + 123
     rng = np.random.default_rng(77)
     g = rng.standard_normal(N).astype(np.float32)
