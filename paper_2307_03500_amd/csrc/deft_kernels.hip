@@ -44,7 +44,7 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 constexpr int64_t kMaxN = (int64_t(1) << 31) - 1;
-constexpr uint32_t kMaxSlotCap = kThreads;  // one thread per slot entry in the slot kernels
+constexpr uint32_t kMaxSlotCap = kThreads;  // unit of the slot capacities: a round of the slot kernels
 // Workgroups of the long-vector first pass: at least the resident set (256 CUs x 3), so every
 // slot is filled; latecomers find the counter exhausted and leave.
 #ifndef DEFT_STREAM_GRID
@@ -1076,6 +1076,13 @@ __device__ __forceinline__ void load_batch(VecBatch& b, const float* __restrict_
 #define DEFT_STAGE_MULT 2
 #endif
 constexpr uint32_t kLongSlotCap = DEFT_LONG_CAP_MULT * kMaxSlotCap;  // the slot capacity of the long-vector shape
+// ... and of the short one: a quarter of a chunk as well (with 256 slots the NCF-shaped
+// conventional Top-k at d = 0.1 overflowed wherever it selects: 159 us, 143 us with 1024; the
+// sparse sets do not notice).
+#ifndef DEFT_SHORT_CAP_MULT
+#define DEFT_SHORT_CAP_MULT 4
+#endif
+constexpr uint32_t kShortSlotCap = DEFT_SHORT_CAP_MULT * kMaxSlotCap;
 // Entries a wavefront of the bounded first pass holds in LDS before it moves them to the slots: a
 // step adds 256 at most, so the staging array is emptied whenever fewer than that are free.
 constexpr uint32_t kStageCap = DEFT_STAGE_MULT * kMaxSlotCap;
@@ -1302,8 +1309,8 @@ __global__ __launch_bounds__(kThreads) void pass2_kernel(
   }
 }
 
-// Last digit level, from the slots.  One workgroup per count/emit chunk, one thread per slot
-// entry; a chunk whose candidates overflowed its slots is read from the segment instead.
+// Last digit level, from the slots.  One workgroup per count/emit chunk, a thread per slot
+// entry and round; a chunk whose candidates overflowed its slots is read from the segment instead.
 template <int ITERS, bool FUSED>
 __global__ __launch_bounds__(kThreads) void slot_hist2_kernel(
     const float* __restrict__ g, const SegDesc* __restrict__ seg, SegState* __restrict__ st, int m,
@@ -1322,19 +1329,21 @@ __global__ __launch_bounds__(kThreads) void slot_hist2_kernel(
   if (s.done || n == 0) return;
   uint32_t* gh = hist + (size_t)j * kHistStride + hist_offset(2) + (blockIdx.x % kRep12) * kBins;
   if (n <= cap) {
-    const bool on = threadIdx.x < n;
-    const uint32_t e = on ? (slots[(size_t)blockIdx.x * cap + threadIdx.x].x & 0x7FFFFFFFu) : 0u;
-    bool live = on && (e >> kBits2) == s.prefix;  // the threshold's first two digits
-    const uint32_t digit = e & (kBins - 1);
-    // equal digits are common (rounded gradients): one atomic per distinct digit and wave
-    unsigned long long act = __ballot(live);
-    while (act) {
-      const int leader = __ffsll((long long)act) - 1;
-      const uint32_t dl = (uint32_t)__builtin_amdgcn_readlane((int)digit, leader);
-      const unsigned long long same = __ballot(live && digit == dl);
-      if ((int)(threadIdx.x & 63) == leader) atomicAdd(&gh[dl], (uint32_t)__popcll(same));
-      if (live && digit == dl) live = false;
-      act &= ~same;
+    for (uint32_t r0 = 0; r0 < n; r0 += kThreads) {
+      const bool on = r0 + threadIdx.x < n;
+      const uint32_t e = on ? (slots[(size_t)blockIdx.x * cap + r0 + threadIdx.x].x & 0x7FFFFFFFu) : 0u;
+      bool live = on && (e >> kBits2) == s.prefix;  // the threshold's first two digits
+      const uint32_t digit = e & (kBins - 1);
+      // equal digits are common (rounded gradients): one atomic per distinct digit and wave
+      unsigned long long act = __ballot(live);
+      while (act) {
+        const int leader = __ffsll((long long)act) - 1;
+        const uint32_t dl = (uint32_t)__builtin_amdgcn_readlane((int)digit, leader);
+        const unsigned long long same = __ballot(live && digit == dl);
+        if ((int)(threadIdx.x & 63) == leader) atomicAdd(&gh[dl], (uint32_t)__popcll(same));
+        if (live && digit == dl) live = false;
+        act &= ~same;
+      }
     }
     return;
   }
@@ -1464,10 +1473,10 @@ __global__ __launch_bounds__(kThreads) void slot_count_kernel(
   const uint32_t T = state_after<3, FUSED>(st, m, j, hist, local == 0, fl).T;
   uint32_t gt = 0, eq = 0;
   if (n <= cap) {
-    if (threadIdx.x < n) {
-      const uint32_t key = slots[(size_t)blockIdx.x * cap + threadIdx.x].x & 0x7FFFFFFFu;
-      gt = key > T ? 1u : 0u;
-      eq = key == T ? 1u : 0u;
+    for (uint32_t r = threadIdx.x; r < n; r += kThreads) {
+      const uint32_t key = slots[(size_t)blockIdx.x * cap + r].x & 0x7FFFFFFFu;
+      gt += key > T ? 1u : 0u;
+      eq += key == T ? 1u : 0u;
     }
   } else {
     if (threadIdx.x == 0) raise_flag(flags, kFlagOverflow);  // the ordered write needs its second launch
@@ -2077,10 +2086,10 @@ struct SelectLayout {
 // overflowed in 840 .. 2000 of its 13365 chunks, each then read again from the segment by every
 // kernel behind the first pass (178 us; 158 us with 1024 slots, 148 us with 2048).
 inline uint32_t slot_cap_for(uint64_t /*total_k*/, uint64_t /*share*/, uint32_t chunk_elems) {
-  return chunk_elems == kThreads * 4 * DEFT_SEL_ITERS_SMALL ? kMaxSlotCap : kLongSlotCap;
+  return chunk_elems == kThreads * 4 * DEFT_SEL_ITERS_SMALL ? kShortSlotCap : kLongSlotCap;
 }
 
-SelectLayout select_layout(int64_t m, uint64_t chunks, uint32_t cap = std::max(kMaxSlotCap, kLongSlotCap / 2)) {
+SelectLayout select_layout(int64_t m, uint64_t chunks, uint32_t cap = std::max(kShortSlotCap, kLongSlotCap / 2)) {
   SelectLayout w;
   size_t o = 0;
   w.stats = o; o = 256;  // DEFT_STAT_ words, at the very start of the workspace

@@ -267,12 +267,16 @@ def test_select_unaligned_segments_and_subset(deft):
         _check_select(sel, gd, g, off, k, part)
 
 
-@pytest.mark.parametrize("n_c", [31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 300])
+@pytest.mark.parametrize("n_c", [31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 300, 511, 512, 513,
+                                 1020, 1022, 1023, 1024, 1025, 1100, 2040, 2046, 2047, 2048, 2049])
 def test_select_candidate_slots_boundary(deft, n_c):
     """One count/emit chunk holds exactly n_c keys in the threshold's top-digit bucket, around
-    every possible slot capacity (32..256): the chunk is served from its slots or, one past the
-    capacity, from the segment itself; both must give the oracle's answer.  Other chunks hold
-    a few candidates each, and the tie class of the threshold spans chunks."""
+    every round of the slot kernels (256 entries each) and the slot capacities (1024 per chunk;
+    2048 in the long-vector shape, whose chunks are twice as long; a few of the larger and of
+    the scattered keys land in the same chunk, so several counts sit just below each capacity):
+    the chunk is served from its slots or, past the capacity, from the segment itself; both must
+    give the oracle's answer.  Other chunks hold a few candidates each, and the tie class of the
+    threshold spans chunks."""
     N = 4096 * 5 + 77
     rng = np.random.default_rng(n_c)
     g = np.full(N, 1e-3, np.float32) * rng.choice([-1, 1], N).astype(np.float32)
@@ -363,7 +367,7 @@ def test_select_adversarial_values_long_vector_shape(deft, long_vector_shape, ki
     test_select_adversarial_values(deft, kind)
 
 
-@pytest.mark.parametrize("n_c", [32, 33, 64, 65, 129, 257])
+@pytest.mark.parametrize("n_c", [32, 33, 64, 65, 129, 257, 513, 1025, 2040, 2046, 2047, 2048, 2049, 3000])
 def test_select_candidate_slots_boundary_long_vector_shape(deft, long_vector_shape, n_c):
     test_select_candidate_slots_boundary(deft, n_c)
 
