@@ -2072,7 +2072,7 @@ inline int chunk_iters_for(int64_t elems, int32_t shape) {
 // place the threshold within four top digits.  DEFT_SHAPE_LONG_SAMPLED samples whatever can be sampled
 // (the device side still turns down what its sample cannot place).
 constexpr uint32_t kSampleMinElems = 1u << 22;
-constexpr uint32_t kSampleMinK = 12800;
+constexpr uint32_t kSampleMinK = 32768;  // 256 sampled keys at or above the threshold: fewer were turned down on every set tried
 inline bool sample_segment(const SegDesc& d, int32_t shape) {
   if (shape == DEFT_SHAPE_LONG_PLAIN || sample_pieces(d.start, d.size) == 0) return false;
   if (shape == DEFT_SHAPE_LONG_SAMPLED) return true;
