@@ -32,7 +32,8 @@
  *   - Results are deterministic: the same inputs give the same bits.
  *   - The library reads no environment variable and has no settings of its own: what tunes a
  *     call travels in its arguments.  The selection calls take a launch shape: DEFT_SHAPE_AUTO
- *     picks by size (long-vector kernels above 2^25 selected-from elements); DEFT_SHAPE_SHORT and
+ *     picks by size (long-vector kernels above 2^26 selected-from elements, and above 2^25 where
+ *     most of them lie in segments that can take the one-read pass); DEFT_SHAPE_SHORT and
  *     DEFT_SHAPE_LONG force one; _LONG_PLAIN and _LONG_SAMPLED also fix whether the long-vector
  *     kernels sample a segment ahead of their first pass (by default they do where it pays).
  *     The shape changes speed only, never results.

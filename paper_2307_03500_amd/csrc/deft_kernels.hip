@@ -2056,15 +2056,17 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 #ifndef DEFT_SEL_ITERS_LARGE
 #define DEFT_SEL_ITERS_LARGE 8
 #endif
-// Vectors above this many elements use the long-vector launch shape (larger chunks, separate
-// bucket-search kernels, wave-per-chunk slot kernels) unless the caller names a shape.
-constexpr int64_t kLongVectorElems = int64_t(1) << 25;
+// Unless the caller names a shape: selections from more than kLongVectorElems elements use the
+// long-vector launch shape (larger chunks, separate bucket-search kernels, wave-per-chunk slot
+// kernels); from kSampledVectorElems on they do if the one-read pass would cover at least half of
+// them.  Measured: layer-wise shares of 44 M elements in 13 .. 144 segments, none sampled, 104 ..
+// 128 us in the short shape against 116 .. 141 us in the long one (89 M: 199 .. 216 against
+// 186 .. 208 us); one segment of 36 / 50 / 66 M elements, K = N/100, read once: 83 / 92 / 106 us
+// against 108 / 134 / 168 us in the short shape.
+constexpr int64_t kSampledVectorElems = int64_t(1) << 25;
+constexpr int64_t kLongVectorElems = int64_t(1) << 26;
 inline bool valid_shape(int32_t shape) {
   return shape >= DEFT_SHAPE_AUTO && shape <= DEFT_SHAPE_LONG_SAMPLED;
-}
-inline int chunk_iters_for(int64_t elems, int32_t shape) {
-  const bool lng = shape >= DEFT_SHAPE_LONG || (shape == DEFT_SHAPE_AUTO && elems > kLongVectorElems);
-  return lng ? DEFT_SEL_ITERS_LARGE : DEFT_SEL_ITERS_SMALL;
 }
 // Whether a segment of a long vector is sampled ahead of its first pass: it must be long enough
 // for the sample (1/128 of it) to be cheap next to a second read, sparse enough for its
@@ -2225,8 +2227,19 @@ int run_select(const float* g, const std::vector<SegDesc>& segs_in, int64_t shar
                hipStream_t s, const Precleared* pre = nullptr) {
   const int m = (int)segs_in.size();
   if (m == 0) return DEFT_OK;
-  const int iters = chunk_iters_for(share, shape);
-  const bool small = iters == DEFT_SEL_ITERS_SMALL;
+  bool lng = shape >= DEFT_SHAPE_LONG;
+  if (shape == DEFT_SHAPE_AUTO) {
+    lng = share > kLongVectorElems;
+    if (!lng && share > kSampledVectorElems) {
+      uint64_t covered = 0;
+      uint32_t n_cov = 0;
+      for (const auto& d : segs_in)
+        if (n_cov < kMaxSampled && sample_segment(d, shape)) { covered += d.size; ++n_cov; }
+      lng = 2 * covered >= (uint64_t)share;
+    }
+  }
+  const int iters = lng ? DEFT_SEL_ITERS_LARGE : DEFT_SEL_ITERS_SMALL;
+  const bool small = !lng;
   const uint32_t ce = (uint32_t)kThreads * 4 * iters;
   const uint32_t hce = 4 * ce;
   std::vector<SegDesc> segs(segs_in);
