@@ -465,14 +465,21 @@ struct Chunk {
   }
   int64_t base;           // absolute index of this thread's vector in step 0
 
-  __device__ __forceinline__ void load(const float* __restrict__ g, int64_t s, int64_t e,
-                                       uint32_t local_chunk) {
+  // Where the chunk sits and whether it lies wholly inside [s, e) (uniform over the workgroup).
+  __device__ __forceinline__ bool place(int64_t s, int64_t e, uint32_t local_chunk) {
     const int64_t a = s & ~int64_t(3);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int64_t cstart = a + (int64_t)local_chunk * kElems;
     base = cstart + ((int64_t)wave * ITERS * 64 + lane) * 4;
-    if (cstart >= s && cstart + kElems <= e) {
-      // interior chunk (uniform over the workgroup): all loads in flight together
+    return cstart >= s && cstart + kElems <= e;
+  }
+
+  // INTERIOR: all loads in flight together, issued in the order of the steps (the scheduler is
+  // kept from reordering them) so that a kernel that walks the steps in order waits for one load
+  // at a time instead of for the last one issued.
+  template <bool INTERIOR>
+  __device__ __forceinline__ void fetch(const float* __restrict__ g, int64_t s, int64_t e) {
+    if (INTERIOR) {
       const v4u* __restrict__ p = reinterpret_cast<const v4u*>(g + base);
 #pragma unroll
       for (int w = 0; w < (ITERS + 7) / 8; ++w) vbits[w] = 0xFFFFFFFFu;
@@ -480,6 +487,7 @@ struct Chunk {
       for (int i = 0; i < ITERS; ++i) {
         const v4u v = __builtin_nontemporal_load(&p[i * 64]);  // streamed: keep it out of L2's way
         raw[i][0] = v.x; raw[i][1] = v.y; raw[i][2] = v.z; raw[i][3] = v.w;
+        __builtin_amdgcn_sched_barrier(0);
       }
     } else {
 #pragma unroll
@@ -509,6 +517,12 @@ struct Chunk {
 #pragma unroll
       for (int c = 0; c < 4; ++c) key[i][c] = raw[i][c] & 0x7FFFFFFFu;
     }
+  }
+
+  __device__ __forceinline__ void load(const float* __restrict__ g, int64_t s, int64_t e,
+                                       uint32_t local_chunk) {
+    if (place(s, e, local_chunk)) fetch<true>(g, s, e);
+    else fetch<false>(g, s, e);
   }
 };
 
@@ -677,7 +691,9 @@ __device__ __forceinline__ void hist0_chunk(const float* __restrict__ g, const S
   for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
   __syncthreads();
   Chunk<HITERS> ch;
-  ch.load(g, d.start, (int64_t)d.start + d.size, blockIdx.x - d.hchunk_base);
+  // (the walk is written out once per form of the fetch, so that no control-flow join sits between
+  // the loads and their first use: at a join the compiler waits for every load in flight)
+  auto walk = [&]() __attribute__((always_inline)) {
 #pragma unroll
   for (int i = 0; i < HITERS; ++i) {
     // Runs of equal keys (zero rows of an embedding, clipped or rounded gradients) would send
@@ -697,6 +713,15 @@ __device__ __forceinline__ void hist0_chunk(const float* __restrict__ g, const S
     for (int c = 0; c < 4; ++c) {
       if ((ch.vmask(i) >> c) & 1u) atomicAdd(&lh[ch.key[i][c] >> kShift], 1u);
     }
+  }
+  };
+  const int64_t seg_end = (int64_t)d.start + d.size;
+  if (ch.place(d.start, seg_end, blockIdx.x - d.hchunk_base)) {
+    ch.template fetch<true>(g, d.start, seg_end);
+    walk();
+  } else {
+    ch.template fetch<false>(g, d.start, seg_end);
+    walk();
   }
   __syncthreads();
   uint32_t* gh = hist + (size_t)j * kHistStride + hist_offset(0) + (blockIdx.x % kRep0) * kBins;
@@ -1280,9 +1305,10 @@ __global__ __launch_bounds__(kThreads) void pass2_kernel(
   for (int b = threadIdx.x; b < kBins; b += kThreads) lh[b] = 0;
   __syncthreads();
   Chunk<HITERS> ch;
-  ch.load(g, d.start, (int64_t)d.start + d.size, local);
   uint2* my_slots = slots + (size_t)(d.chunk_base + ec_local) * cap;
   uint32_t filled = 0;
+  // (written out once per form of the fetch: no join between the loads and their first use)
+  auto walk = [&]() __attribute__((always_inline)) {
 #pragma unroll
   for (int i = 0; i < HITERS; ++i) {
     uint32_t livem = 0;
@@ -1304,6 +1330,22 @@ __global__ __launch_bounds__(kThreads) void pass2_kernel(
       }
     }
     filled += tot;
+  }
+  };
+  const int64_t seg_end = (int64_t)d.start + d.size;
+  if constexpr (FUSED) {
+    if (ch.place(d.start, seg_end, local)) {
+      ch.template fetch<true>(g, d.start, seg_end);
+      walk();
+    } else {
+      ch.template fetch<false>(g, d.start, seg_end);
+      walk();
+    }
+  } else {
+    // (long vectors: twice the registers per chunk; the two copies of the walk cost the kernel a
+    // third of its resident wavefronts, and other workgroups cover a wavefront's wait there)
+    ch.load(g, d.start, seg_end, local);
+    walk();
   }
   if (lane == 0 && have_chunk) live_cnt[d.chunk_base + ec_local] = filled;
   __syncthreads();
